@@ -1,0 +1,290 @@
+"""QTIP oracle -- TEST INFRASTRUCTURE ONLY.
+
+ctypes front end of ``qtip_oracle.c``: a plain CPU statement of what the QTIP
+inference path computes (arXiv 2406.11235), used by the tests, the smoke check
+and the benchmark's cpu_baseline leg.  The product package never imports this
+module and this module never imports the product package.
+
+Every function takes and returns numpy arrays; fp16 values travel as uint16
+bit patterns so that nothing is rounded on the way in or out.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "qtip_oracle.c")
+_LIB = os.path.join(_HERE, "libqtip_oracle.so")
+
+CODE_1MAD, CODE_3INST, CODE_HYB = 0, 1, 2
+
+
+def build(force=False):
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+           "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        c = ctypes
+        vp, i32, dbl = c.c_void_p, c.c_int, c.c_double
+        L.orc_threads.restype = i32
+        L.orc_f16_to_f64.restype = dbl
+        L.orc_f16_to_f64.argtypes = [c.c_uint16]
+        L.orc_f64_to_f16.restype = c.c_uint16
+        L.orc_f64_to_f16.argtypes = [dbl]
+        L.orc_stream_bit.restype = i32
+        L.orc_stream_bit.argtypes = [vp, i32]
+        L.orc_state.restype = c.c_uint32
+        L.orc_state.argtypes = [vp, i32, i32, i32, i32]
+        L.orc_code_1mad.restype = c.c_uint16
+        L.orc_code_1mad.argtypes = [c.c_uint32]
+        L.orc_code_3inst.restype = c.c_uint16
+        L.orc_code_3inst.argtypes = [c.c_uint32]
+        L.orc_code_hyb.restype = None
+        L.orc_code_hyb.argtypes = [c.c_uint32, i32, vp, vp]
+        L.orc_codebook.restype = i32
+        L.orc_codebook.argtypes = [i32, i32, i32, vp, i32, vp]
+        L.orc_decode_sequence.restype = None
+        L.orc_decode_sequence.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, vp]
+        L.orc_decode_sequence_table.restype = None
+        L.orc_decode_sequence_table.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+        L.orc_dequantize.restype = i32
+        L.orc_dequantize.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, vp]
+        L.orc_decode_element.restype = c.c_uint16
+        L.orc_decode_element.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32]
+        L.orc_matmat_dense.restype = None
+        L.orc_matmat_dense.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+        L.orc_decode_matmat_rows.restype = None
+        L.orc_decode_matmat_rows.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, vp,
+                                             i32, vp, vp, i32, vp]
+        L.orc_hadamard.restype = None
+        L.orc_hadamard.argtypes = [i32, vp]
+        L.orc_rht.restype = i32
+        L.orc_rht.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        L.orc_viterbi.restype = dbl
+        L.orc_viterbi.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp]
+        L.orc_states_to_stream.restype = None
+        L.orc_states_to_stream.argtypes = [vp, i32, i32, i32, vp]
+        L.orc_tailbiting_quantize.restype = dbl
+        L.orc_tailbiting_quantize.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.orc_stream_distortion.restype = dbl
+        L.orc_stream_distortion.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        L.orc_exhaustive_tailbiting.restype = dbl
+        L.orc_exhaustive_tailbiting.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.orc_exhaustive_walk.restype = dbl
+        L.orc_exhaustive_walk.argtypes = [vp, i32, i32, i32, i32, vp]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u16(a):
+    """fp16 array or uint16 bit patterns -> contiguous uint16 bit patterns."""
+    if a is None:
+        return None
+    a = np.asarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    assert a.dtype == np.uint16, a.dtype
+    return np.ascontiguousarray(a)
+
+
+def _u32(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint32, a.dtype
+    return a
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def threads():
+    return int(lib().orc_threads())
+
+
+def f16_to_f64(h):
+    return float(lib().orc_f16_to_f64(int(h)))
+
+
+def f64_to_f16(v):
+    return int(lib().orc_f64_to_f16(float(v)))
+
+
+def stream_bit(words, i):
+    return int(lib().orc_stream_bit(_p(_u32(words)), int(i)))
+
+
+def state(words, nbits, L, kV, t):
+    w = _u32(words)
+    assert w.size * 32 >= nbits
+    return int(lib().orc_state(_p(w), nbits, L, kV, t))
+
+
+def code_1mad(x):
+    return int(lib().orc_code_1mad(int(x)))
+
+
+def code_3inst(x):
+    return int(lib().orc_code_3inst(int(x)))
+
+
+def code_hyb(x, lut, Q=9):
+    lut = _u16(lut).reshape(-1)
+    assert lut.size == 2 << Q
+    out = np.zeros(2, dtype=np.uint16)
+    lib().orc_code_hyb(int(x), Q, _p(lut), _p(out))
+    return int(out[0]), int(out[1])
+
+
+def codebook(L, V, code_id, lut=None, Q=9):
+    """C[2^L][V] as float64, by evaluating the code on every state."""
+    lut = None if lut is None else _u16(lut).reshape(-1)
+    C = np.zeros((1 << L, V), dtype=np.float64)
+    rc = lib().orc_codebook(L, V, code_id, _p(lut), Q, _p(C))
+    assert rc == 0
+    return C
+
+
+def decode_sequence(words, T, L, k, V, code_id, lut=None, Q=9):
+    w = _u32(words)
+    assert w.size * 32 >= k * T
+    lut = None if lut is None else _u16(lut).reshape(-1)
+    out = np.zeros(T, dtype=np.uint16)
+    lib().orc_decode_sequence(_p(w), T, L, k, V, code_id, _p(lut), Q, _p(out))
+    return out
+
+
+def decode_sequence_table(words, T, L, k, V, C):
+    w = _u32(words)
+    assert w.size * 32 >= k * T
+    C = _f64(C).reshape(1 << L, V)
+    out = np.zeros(T, dtype=np.float64)
+    st = np.zeros(T // V, dtype=np.uint32)
+    lib().orc_decode_sequence_table(_p(w), T, L, k, V, _p(C), _p(out), _p(st))
+    return out, st
+
+
+def dequantize(codes, L, k, V, code_id, m, n, lut=None, Q=9):
+    """Dense decoded weights as uint16 fp16 bit patterns, shape (m, n)."""
+    codes = _u32(codes).reshape(-1)
+    assert codes.size == (m // 16) * (n // 16) * 8 * k
+    lut = None if lut is None else _u16(lut).reshape(-1)
+    W = np.zeros((m, n), dtype=np.uint16)
+    rc = lib().orc_dequantize(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, _p(W))
+    assert rc == 0
+    return W
+
+
+def decode_element(codes, L, k, V, code_id, n, i, j, lut=None, Q=9):
+    codes = _u32(codes).reshape(-1)
+    lut = None if lut is None else _u16(lut).reshape(-1)
+    return int(lib().orc_decode_element(_p(codes), L, k, V, code_id, _p(lut), Q, n, i, j))
+
+
+def matmat_dense(W, X, scale=None):
+    """Y[b][i] = scale[i] * sum_j W[i][j] X[b][j] in fp64; fp16 inputs as bits."""
+    W = _u16(W)
+    m, n = W.shape
+    X = _u16(X).reshape(-1, n)
+    B = X.shape[0]
+    scale = _u16(scale)
+    Y = np.zeros((B, m), dtype=np.float64)
+    lib().orc_matmat_dense(_p(W), m, n, _p(X), B, _p(scale), _p(Y))
+    return Y
+
+
+def decode_matmat_rows(codes, L, k, V, code_id, m, n, X, rows, lut=None, Q=9, scale=None):
+    """fp64 outputs for the chosen rows only: shape (B, len(rows))."""
+    codes = _u32(codes).reshape(-1)
+    lut = None if lut is None else _u16(lut).reshape(-1)
+    X = _u16(X).reshape(-1, n)
+    B = X.shape[0]
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
+    scale = _u16(scale)
+    Y = np.zeros((B, rows.size), dtype=np.float64)
+    lib().orc_decode_matmat_rows(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, _p(X), B,
+                                 _p(scale), _p(rows), rows.size, _p(Y))
+    return Y
+
+
+def hadamard(b):
+    H = np.zeros((b, b), dtype=np.int8)
+    lib().orc_hadamard(b, _p(H))
+    return H
+
+
+def rht(x, signs, block, side=0):
+    """Random Hadamard transform of fp16 rows x (batch, n) -> float64."""
+    x = _u16(x)
+    x2 = x.reshape(1, -1) if x.ndim == 1 else x
+    batch, n = x2.shape
+    signs = np.ascontiguousarray(np.asarray(signs, dtype=np.int8))
+    assert signs.size == n
+    out = np.zeros((batch, n), dtype=np.float64)
+    rc = lib().orc_rht(_p(np.ascontiguousarray(x2)), _p(signs), n, block, batch, side, _p(out))
+    assert rc == 0, rc
+    return out.reshape(x.shape)
+
+
+def viterbi(S, L, k, V, C, first_top=-1, last_low=-1):
+    S = _f64(S)
+    T = S.size
+    C = _f64(C).reshape(1 << L, V)
+    st = np.zeros(T // V, dtype=np.uint32)
+    d = lib().orc_viterbi(_p(S), T, L, k, V, _p(C), first_top, last_low, _p(st))
+    return float(d), st
+
+
+def states_to_stream(states, L, kV):
+    st = _u32(states)
+    G = st.size
+    words = np.zeros((G * kV + 31) // 32, dtype=np.uint32)
+    lib().orc_states_to_stream(_p(st), G, L, kV, _p(words))
+    return words
+
+
+def tailbiting_quantize(S, L, k, V, C):
+    S = _f64(S)
+    T = S.size
+    C = _f64(C).reshape(1 << L, V)
+    words = np.zeros((k * T + 31) // 32, dtype=np.uint32)
+    d = lib().orc_tailbiting_quantize(_p(S), T, L, k, V, _p(C), _p(words))
+    return float(d), words
+
+
+def stream_distortion(words, S, L, k, V, C):
+    S = _f64(S)
+    C = _f64(C).reshape(1 << L, V)
+    return float(lib().orc_stream_distortion(_p(_u32(words)), _p(S), S.size, L, k, V, _p(C)))
+
+
+def exhaustive_tailbiting(S, L, k, V, C):
+    S = _f64(S)
+    C = _f64(C).reshape(1 << L, V)
+    w = np.zeros(1, dtype=np.uint32)
+    d = lib().orc_exhaustive_tailbiting(_p(S), S.size, L, k, V, _p(C), _p(w))
+    return float(d), w
+
+
+def exhaustive_walk(S, L, k, V, C):
+    S = _f64(S)
+    C = _f64(C).reshape(1 << L, V)
+    return float(lib().orc_exhaustive_walk(_p(S), S.size, L, k, V, _p(C)))
