@@ -1,0 +1,145 @@
+/*
+ * qtip.h -- C ABI of the MI355X (gfx950) QTIP inference library.
+ *
+ * QTIP (arXiv 2406.11235) stores a weight matrix W~ (m outputs x n inputs, already
+ * conjugated by random Hadamard transforms) as trellis-coded bitstreams: every
+ * 16 x 16 block of W~ is one length-256 sequence quantized with an (L, k, V)
+ * "bitshift" trellis (Section 3.1), stored tail-biting in exactly 256*k bits
+ * (Section 3.2), and mapped from L-bit states to values by a computed code
+ * (1MAD, 3INST: Section 3.1.1, Algorithms 1-2) or a hash + small lookup table
+ * (HYB: Section 3.1.2, Algorithm 3).  Inference decodes the stream on the fly
+ * and multiplies by the Hadamard-transformed activation (Section 2.1).
+ *
+ * DATA FORMATS (shared by every call)
+ *   codes   uint32 words, DEVICE memory unless stated otherwise.  The matrix is a
+ *           row-major array of 16x16 tiles; tile (I, J) (I over outputs, J over
+ *           inputs) starts at word (I*(n/16) + J) * 8k and holds 8k words =
+ *           256*k bits.  Logical stream bit i of a tile is bit 31-(i%32) of word
+ *           i/32, so the first stored bit is the most significant bit of the
+ *           first state (Figure 1).  Must be 16-byte aligned.
+ *   state   group t (t = 0 .. 256/V - 1) of a tile has the L-bit state made of
+ *           stream bits t*k*V ... t*k*V+L-1, first bit most significant, positions
+ *           taken modulo 256*k (tail-biting wrap).
+ *   order   group t decodes to sequence elements V*t ... V*t+V-1; sequence element
+ *           s of tile (I, J) is W~[16I + s/16][16J + s%16] (the row-major reshape
+ *           of a T_x x T_y block in Algorithm 5).
+ *   lut     HYB only: 2^9 x 2 fp16 values, DEVICE memory, entry v of row idx at
+ *           half-word 2*idx + v.  Bit 15 of the hash negates entry v = 1 (the
+ *           "second entry" of Section 3.1.2).  4-byte aligned.
+ *   fp16    IEEE binary16, passed as void*.
+ *
+ * SUPPORTED PARAMETERS
+ *   L = 16 only.  code_id QTIP_CODE_1MAD / QTIP_CODE_3INST with V = 1 and
+ *   k in {2, 3, 4}; QTIP_CODE_HYB (Q = 9) with V = 2 and k in {2, 3, 4}.
+ *   m and n multiples of 16.  Anything else returns QTIP_EUNSUPPORTED / QTIP_EINVAL.
+ *
+ * OWNERSHIP, STREAMS, ERRORS
+ *   The caller owns every buffer.  GPU entry points take device pointers, enqueue
+ *   their kernels on `stream` (a hipStream_t passed as void*; NULL = the default
+ *   stream) and return without synchronizing.  The library allocates no device
+ *   memory and keeps no state besides a thread-local error string.  Every call
+ *   returns 0 (QTIP_OK) or a negative error code and never throws or aborts;
+ *   qtip_last_error() describes the last failure on the calling thread.
+ *   Buffers must not overlap unless a call says it allows it.
+ */
+#ifndef QTIP_H
+#define QTIP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QTIP_VERSION 100
+
+#define QTIP_OK 0
+#define QTIP_EINVAL (-1)       /* null pointer, bad size or alignment           */
+#define QTIP_EUNSUPPORTED (-2) /* (L, k, V, code_id) outside the supported set  */
+#define QTIP_EHIP (-3)         /* HIP runtime / launch failure                  */
+#define QTIP_ENOMEM (-4)       /* host allocation failed (qtip_quantize)        */
+
+#define QTIP_CODE_1MAD 0  /* Algorithm 1 */
+#define QTIP_CODE_3INST 1 /* Algorithm 2 */
+#define QTIP_CODE_HYB 2   /* Algorithm 3, Q = 9, one sign flip */
+
+/*
+ * Random Hadamard transform of activations (Section 2.1: W~ = V_m S_m W S_n V_n^T,
+ * so the layer computes y = S_m V_m^T (W~ (V_n S_n x))).  V is the orthogonal
+ * block-diagonal Walsh-Hadamard matrix H_block / sqrt(block) in natural
+ * (Sylvester) order; n must be a multiple of block, block a power of two in
+ * [16, 16384].
+ *   side 0 (input side):   out = V (S .* x)    for each of the `batch` rows of x
+ *   side 1 (output side):  out = S .* (V^T x)
+ * x: device, batch x n row-major, fp16 (qtip_rht) or fp32 (qtip_rht_f32, for
+ * feeding the fp32 result of a multiply straight into the output-side transform).
+ * signs: device, n int8 values, each +1 or -1.  out_f16: device, batch x n fp16.
+ * out may alias x in qtip_rht.  Arithmetic is fp32, rounded once to fp16.
+ */
+int qtip_rht(const void *x_f16, const int8_t *signs, int n, int block, int batch, int side,
+             void *out_f16, void *stream);
+int qtip_rht_f32(const float *x_f32, const int8_t *signs, int n, int block, int batch,
+                 int side, void *out_f16, void *stream);
+
+/*
+ * Fused decode + matrix-vector product, batch 1 (Sections 3.1, 3.1.1-3.1.2 and 4:
+ * decode each tile's bitstream to fp16 weights and contract with the activation):
+ *   y[i] = sum_j W~[i][j] * x[j],   i < m, j < n.
+ * x_f16: device, n fp16 (normally the output of qtip_rht side 0).  y: device, m
+ * fp32, overwritten.  Decoded weights are exactly the fp16 values of
+ * qtip_dequantize; products are accumulated in fp32.  lut_f16 is NULL unless
+ * code_id is QTIP_CODE_HYB.
+ */
+int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
+                       const void *lut_f16, int m, int n, const void *x_f16, float *y,
+                       void *stream);
+
+/*
+ * Batched form: Y[b][i] = row_scale[i] * sum_j W~[i][j] * X[b][j], b < B.
+ * X_f16: device, B x n row-major fp16.  Y: device, B x m row-major fp32,
+ * overwritten.  row_scale_f16: device, m fp16, or NULL for no scale.  B >= 1.
+ * Small B runs on the vector ALUs, larger B on the matrix cores (MFMA) with the
+ * decoded 16x16 tile as one operand (Section 4: T_x = T_y = 16 matches a 16x16
+ * matrix-multiply tile).
+ */
+int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id,
+                       const void *lut_f16, int m, int n, const void *X_f16, int B,
+                       const void *row_scale_f16, float *Y, void *stream);
+
+/*
+ * Decode only (for testing): W_f16[i][j] = W~[i][j], device, m x n row-major fp16,
+ * no row scale.  Bit-exact with the definitions of Algorithms 1-3.
+ */
+int qtip_dequantize(const uint32_t *codes, int L, int k, int V, int code_id,
+                    const void *lut_f16, int m, int n, void *W_f16, void *stream);
+
+/*
+ * Decode the code function alone on a list of states (for testing):
+ * out_f16[V*i + v] = code(states[i])[v].  states: device, count uint32 values
+ * below 2^L.  out_f16: device, count*V fp16.
+ */
+int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code_id,
+                       const void *lut_f16, void *out_f16, void *stream);
+
+/*
+ * CPU quantizer, used to make valid inputs and to validate; never on the timed
+ * path.  ALL pointers are HOST memory.  Each 16x16 tile of W (m x n row-major
+ * fp32) is quantized as one sequence with the Viterbi algorithm on the bitshift
+ * trellis (Section 2.3) made tail-biting by Algorithm 4, under squared error.
+ * codes_out receives (m/16)*(n/16)*8k words in the format above.  mse_out (may
+ * be NULL) receives the mean squared error of the reconstruction.  lut_f16 is a
+ * host copy of the HYB table (NULL otherwise).  Uses all host cores.
+ */
+int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id,
+                  const void *lut_f16, uint32_t *codes_out, double *mse_out);
+
+/* Message for the last error on this thread ("" if none). Never NULL. */
+const char *qtip_last_error(void);
+
+/* QTIP_VERSION of the built library. */
+int qtip_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QTIP_H */

@@ -1,0 +1,166 @@
+// extern "C" entry points of include/qtip.h: argument validation, error strings,
+// and dispatch to the kernel launchers.  Nothing here touches the data.
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+
+#include "../../include/qtip.h"
+#include "qtip_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(const char *what, hipError_t e) {
+    return fail(QTIP_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Checks shared by every call that reads a code stream.
+int check_codec(const char *fn, const void *codes, int L, int k, int V, int code_id,
+                const void *lut, int m, int n) {
+    if (!codes) return fail(QTIP_EINVAL, "%s: codes is NULL", fn);
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
+    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
+    if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
+    const int wantV = code_id == QTIP_CODE_HYB ? 2 : 1;
+    if (V != wantV)
+        return fail(QTIP_EUNSUPPORTED, "%s: V = %d (code %d needs V = %d)", fn, V, code_id, wantV);
+    if (code_id == QTIP_CODE_HYB && !lut) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (m <= 0 || n <= 0 || m % 16 || n % 16)
+        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    if (!aligned(codes, 16)) return fail(QTIP_EINVAL, "%s: codes must be 16-byte aligned", fn);
+    if (lut && !aligned(lut, 4)) return fail(QTIP_EINVAL, "%s: lut must be 4-byte aligned", fn);
+    return QTIP_OK;
+}
+
+int rht_common(const char *fn, const void *x, bool f32, const int8_t *signs, int n, int block,
+               int batch, int side, void *out, void *stream) {
+    if (!x || !signs || !out) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (block < 16 || block > 16384 || (block & (block - 1)))
+        return fail(QTIP_EINVAL, "%s: block = %d must be a power of two in [16, 16384]", fn, block);
+    if (n <= 0 || n % block) return fail(QTIP_EINVAL, "%s: n = %d is not a multiple of block %d", fn, n, block);
+    if (batch < 1 || batch > 65535) return fail(QTIP_EINVAL, "%s: batch = %d out of range", fn, batch);
+    if (side != 0 && side != 1) return fail(QTIP_EINVAL, "%s: side = %d must be 0 or 1", fn, side);
+    hipError_t e = qtip::launch_rht(x, f32, signs, n, block, batch, side, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qtip_version(void) { return QTIP_VERSION; }
+
+const char *qtip_last_error(void) { return g_err; }
+
+int qtip_rht(const void *x_f16, const int8_t *signs, int n, int block, int batch, int side,
+             void *out_f16, void *stream) {
+    return rht_common("qtip_rht", x_f16, false, signs, n, block, batch, side, out_f16, stream);
+}
+
+int qtip_rht_f32(const float *x_f32, const int8_t *signs, int n, int block, int batch, int side,
+                 void *out_f16, void *stream) {
+    if ((const void *)x_f32 == (const void *)out_f16 && x_f32)
+        return fail(QTIP_EINVAL, "qtip_rht_f32: out must not alias x");
+    return rht_common("qtip_rht_f32", x_f32, true, signs, n, block, batch, side, out_f16, stream);
+}
+
+int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id, const void *lut_f16,
+                       int m, int n, const void *x_f16, float *y, void *stream) {
+    const char *fn = "qtip_decode_matvec";
+    if (int rc = check_codec(fn, codes, L, k, V, code_id, lut_f16, m, n)) return rc;
+    if (!x_f16 || !y) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (!aligned(x_f16, 16)) return fail(QTIP_EINVAL, "%s: x must be 16-byte aligned", fn);
+    hipError_t e = qtip::launch_matvec(k, code_id, codes, (const uint32_t *)lut_f16, m, n, x_f16,
+                                       nullptr, y, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
+int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id, const void *lut_f16,
+                       int m, int n, const void *X_f16, int B, const void *row_scale_f16, float *Y,
+                       void *stream) {
+    const char *fn = "qtip_decode_matmat";
+    if (int rc = check_codec(fn, codes, L, k, V, code_id, lut_f16, m, n)) return rc;
+    if (!X_f16 || !Y) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (B < 1 || B > 65535 * 64) return fail(QTIP_EINVAL, "%s: B = %d out of range", fn, B);
+    if (!aligned(X_f16, 16)) return fail(QTIP_EINVAL, "%s: X must be 16-byte aligned", fn);
+    hipError_t e;
+    if (B == 1)
+        e = qtip::launch_matvec(k, code_id, codes, (const uint32_t *)lut_f16, m, n, X_f16,
+                                row_scale_f16, Y, (hipStream_t)stream);
+    else
+        e = qtip::launch_matmat(k, code_id, codes, (const uint32_t *)lut_f16, m, n, X_f16, B,
+                                row_scale_f16, Y, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
+int qtip_dequantize(const uint32_t *codes, int L, int k, int V, int code_id, const void *lut_f16,
+                    int m, int n, void *W_f16, void *stream) {
+    const char *fn = "qtip_dequantize";
+    if (int rc = check_codec(fn, codes, L, k, V, code_id, lut_f16, m, n)) return rc;
+    if (!W_f16) return fail(QTIP_EINVAL, "%s: W is NULL", fn);
+    if (!aligned(W_f16, 16)) return fail(QTIP_EINVAL, "%s: W must be 16-byte aligned", fn);
+    hipError_t e = qtip::launch_dequantize(k, code_id, codes, (const uint32_t *)lut_f16, m, n, W_f16,
+                                           (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
+int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code_id,
+                       const void *lut_f16, void *out_f16, void *stream) {
+    const char *fn = "qtip_decode_states";
+    if (!states || !out_f16) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (count < 0) return fail(QTIP_EINVAL, "%s: count = %d", fn, count);
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
+    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
+    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
+    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (count == 0) return QTIP_OK;
+    hipError_t e = qtip::launch_decode_states(code_id, states, count, (const uint32_t *)lut_f16,
+                                              out_f16, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
+int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id,
+                  const void *lut_f16, uint32_t *codes_out, double *mse_out) {
+    const char *fn = "qtip_quantize";
+    if (!W || !codes_out) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
+    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
+    if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
+    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
+    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (m <= 0 || n <= 0 || m % 16 || n % 16)
+        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    int rc;
+    try {
+        rc = qtip::quantize_host(W, m, n, k, V, code_id, (const uint16_t *)lut_f16, codes_out, mse_out);
+    } catch (const std::bad_alloc &) {
+        return fail(QTIP_ENOMEM, "%s: out of host memory", fn);
+    } catch (...) {
+        return fail(QTIP_ENOMEM, "%s: host failure", fn);
+    }
+    if (rc != 0) return fail(QTIP_ENOMEM, "%s: worker failed (out of host memory?)", fn);
+    return QTIP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,359 @@
+// Decode kernels for gfx950: dequantize, fused decode + matrix-vector product on
+// the vector ALUs, and fused decode + batched product on the matrix cores.
+//
+// Work split (all three): one workgroup owns one tile row I (16 output rows)
+// and walks the tiles (I, J) along the input dimension, so outputs are written
+// once by their owner and no atomics or zero-filled buffers are needed.  The
+// waves of a workgroup take contiguous J ranges and their partial sums meet in
+// LDS at the end.
+#include "qtip_device.h"
+#include "qtip_internal.h"
+
+namespace qtip {
+
+template <int K> struct Words;
+template <> struct Words<2> { uint32_t v[4]; };
+template <> struct Words<3> { uint32_t v[3]; };
+template <> struct Words<4> { uint32_t v[4]; };
+
+// Load this lane's WPL words of tile `tile` plus the first word of the next
+// lane of the same tile (cyclically: the tail-biting wrap of Section 3.2).
+template <int K>
+__device__ __forceinline__ void load_tile_words(const uint32_t *__restrict__ codes, size_t tile,
+                                                int lane, uint32_t (&w)[Geo<K>::WPL + 1]) {
+    constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT;
+    const int q = lane & (LPT - 1);
+    const uint32_t *p = codes + tile * (8 * K) + q * WPL;
+    if constexpr (WPL == 4) {
+        uint4 t = *reinterpret_cast<const uint4 *>(p);
+        w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+    } else {
+        w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
+    }
+    w[WPL] = __shfl(w[0], (lane & ~(LPT - 1)) | ((q + 1) & (LPT - 1)), 64);
+}
+
+// Decode tile row rr (0..RPL-1) of this lane: 16 fp16 weights as 8 pairs.
+template <int K, int V, int CODE>
+__device__ __forceinline__ void decode_row(const uint32_t (&w)[Geo<K>::WPL + 1], int rr,
+                                           const uint32_t *lut, half2_t (&out)[8]) {
+#pragma unroll
+    for (int c = 0; c < 8; c++) {
+        if constexpr (V == 2) {
+            uint32_t st = window16(w, rr * 16 * K + c * 2 * K);
+            out[c] = code_hyb(st, lut);
+        } else {
+            uint32_t s0 = window16(w, rr * 16 * K + (2 * c) * K);
+            uint32_t s1 = window16(w, rr * 16 * K + (2 * c + 1) * K);
+            half2_t h;
+            if constexpr (CODE == CODE_3INST) {
+                h.x = code_3inst(s0);
+                h.y = code_3inst(s1);
+            } else {
+                h.x = code_1mad(s0);
+                h.y = code_1mad(s1);
+            }
+            out[c] = h;
+        }
+    }
+}
+
+__device__ __forceinline__ void stage_lut(const uint32_t *__restrict__ lut, uint32_t *s_lut) {
+    for (int i = threadIdx.x; i < (1 << HYB_Q); i += blockDim.x) s_lut[i] = lut[i];
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------- dequantize
+
+template <int K, int V, int CODE>
+__global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t *__restrict__ codes,
+                                                         const uint32_t *__restrict__ lut,
+                                                         int tn, long ntiles,
+                                                         half_t *__restrict__ W) {
+    constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
+    constexpr int TPW = 64 / LPT;  // tiles per wave per step
+    __shared__ uint32_t s_lut[1 << HYB_Q];
+    if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
+    const int lane = threadIdx.x & 63;
+    const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const long tile = wave * TPW + lane / LPT;
+    const bool valid = tile < ntiles;
+    uint32_t w[WPL + 1];
+    load_tile_words<K>(codes, valid ? tile : ntiles - 1, lane, w);
+    if (!valid) return;
+    const long I = tile / tn, J = tile % tn;
+    const int q = lane & (LPT - 1);
+    const size_t n = (size_t)tn * 16;
+#pragma unroll
+    for (int rr = 0; rr < RPL; rr++) {
+        half2_t h[8];
+        decode_row<K, V, CODE>(w, rr, s_lut, h);
+        uint4 lo = {as_u32(h[0]), as_u32(h[1]), as_u32(h[2]), as_u32(h[3])};
+        uint4 hi = {as_u32(h[4]), as_u32(h[5]), as_u32(h[6]), as_u32(h[7])};
+        uint4 *dst = reinterpret_cast<uint4 *>(W + (size_t)(16 * I + q * RPL + rr) * n + 16 * J);
+        dst[0] = lo;
+        dst[1] = hi;
+    }
+}
+
+// -------------------------------------------------------- decode one state each
+
+template <int CODE>
+__global__ void decode_states_kernel(const uint32_t *__restrict__ states, int count,
+                                     const uint32_t *__restrict__ lut, half_t *__restrict__ out) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    uint32_t st = states[i] & 0xFFFFu;
+    if constexpr (CODE == CODE_HYB) {
+        half2_t h = code_hyb(st, lut);
+        out[2 * i] = h.x;
+        out[2 * i + 1] = h.y;
+    } else if constexpr (CODE == CODE_3INST) {
+        out[i] = code_3inst(st);
+    } else {
+        out[i] = code_1mad(st);
+    }
+}
+
+// ------------------------------------------------------- decode + matvec (B = 1)
+
+template <int K, int V, int CODE, int NW>
+__global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restrict__ codes,
+                                                         const uint32_t *__restrict__ lut,
+                                                         int tn, const half_t *__restrict__ x,
+                                                         const half_t *__restrict__ scale,
+                                                         float *__restrict__ y) {
+    constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
+    constexpr int TPI = 64 / LPT;  // tiles per wave per iteration
+    __shared__ uint32_t s_lut[1 << HYB_Q];
+    __shared__ float s_part[NW][16];
+    if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
+    const int I = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int g = lane / LPT, q = lane & (LPT - 1);
+    const int chunk = ((tn + NW * TPI - 1) / (NW * TPI)) * TPI;
+    const int J0 = wave * chunk;
+    const int Jend = min(tn, J0 + chunk);
+    float acc[RPL];
+#pragma unroll
+    for (int rr = 0; rr < RPL; rr++) acc[rr] = 0.f;
+
+    for (int Jb = J0; Jb < Jend; Jb += TPI) {
+        const int J = Jb + g;
+        const bool valid = J < Jend;
+        const int Jc = valid ? J : Jend - 1;
+        uint32_t w[WPL + 1];
+        load_tile_words<K>(codes, (size_t)I * tn + Jc, lane, w);
+        const uint4 *xp = reinterpret_cast<const uint4 *>(x + 16 * Jc);
+        uint4 xa = xp[0], xb = xp[1];
+        if (valid) {
+            half2_t xv[8] = {as_half2(xa.x), as_half2(xa.y), as_half2(xa.z), as_half2(xa.w),
+                             as_half2(xb.x), as_half2(xb.y), as_half2(xb.z), as_half2(xb.w)};
+#pragma unroll
+            for (int rr = 0; rr < RPL; rr++) {
+                half2_t h[8];
+                decode_row<K, V, CODE>(w, rr, s_lut, h);
+#pragma unroll
+                for (int c = 0; c < 8; c++)
+                    acc[rr] = __builtin_amdgcn_fdot2(h[c], xv[c], acc[rr], false);
+            }
+        }
+    }
+    // lanes with equal q hold partial sums of the same rows: add over g
+#pragma unroll
+    for (int rr = 0; rr < RPL; rr++)
+#pragma unroll
+        for (int off = LPT; off < 64; off <<= 1) acc[rr] += __shfl_xor(acc[rr], off, 64);
+    if (g == 0) {
+#pragma unroll
+        for (int rr = 0; rr < RPL; rr++) s_part[wave][q * RPL + rr] = acc[rr];
+    }
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float s = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < NW; wv++) s += s_part[wv][threadIdx.x];
+        const int row = 16 * I + threadIdx.x;
+        if (scale) s *= (float)scale[row];
+        y[row] = s;
+    }
+}
+
+// ------------------------------------------- decode + batched product on MFMA
+//
+// Per tile one v_mfma_f32_16x16x16_f16 per group of 16 batch rows:
+//   A (16 x 16, rows = tile rows, cols = tile columns): lane l holds
+//       A[l % 16][4*(l/16) .. 4*(l/16)+3] = four consecutive sequence elements,
+//       which is what a lane decodes from a 16 + 3k-bit window;
+//   B (16 x 16, rows = tile columns, cols = batch): lane l holds
+//       X[b0 + l % 16][16J + 4*(l/16) .. +3];
+//   D (rows = tile rows, cols = batch): lane l holds D[4*(l/16) + r][l % 16].
+
+template <int K, int V, int CODE, int NB, int NW>
+__global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restrict__ codes,
+                                                         const uint32_t *__restrict__ lut,
+                                                         int tn, int m, const half_t *__restrict__ X,
+                                                         int B, const half_t *__restrict__ scale,
+                                                         float *__restrict__ Y) {
+    __shared__ uint32_t s_lut[1 << HYB_Q];
+    __shared__ float s_part[NW][NB][4][64];
+    if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
+    const int I = blockIdx.x;
+    const int b0 = blockIdx.y * (16 * NB);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = lane & 15, kq = lane >> 4;
+    const size_t n = (size_t)tn * 16;
+    const int chunk = (tn + NW - 1) / NW;
+    const int J0 = wave * chunk;
+    const int Jend = min(tn, J0 + chunk);
+    float4_t acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++) acc[nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // this lane's four weights start P bits into the tile
+    const int P = (16 * row + 4 * kq) * K;
+    const int wi = P >> 5, sh = P & 31;
+    constexpr int NWORDS = 8 * K;
+    for (int J = J0; J < Jend; J++) {
+        const uint32_t *tp = codes + ((size_t)I * tn + J) * NWORDS;
+        // 16 + 3K (V = 1) or 16 + KV (V = 2) bits from offset sh of a 64-bit funnel
+        uint32_t w0 = tp[wi], w1 = tp[(wi + 1) % NWORDS];
+        uint64_t f = ((uint64_t)w0 << 32) | w1;
+        half4_t a;
+        if constexpr (V == 2) {
+            uint32_t s0 = (uint32_t)(f >> (48 - sh)) & 0xFFFFu;
+            uint32_t s1 = (uint32_t)(f >> (48 - sh - 2 * K)) & 0xFFFFu;
+            half2_t h0 = code_hyb(s0, s_lut), h1 = code_hyb(s1, s_lut);
+            a = half4_t{h0.x, h0.y, h1.x, h1.y};
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                uint32_t st = (uint32_t)(f >> (48 - sh - e * K)) & 0xFFFFu;
+                a[e] = (CODE == CODE_3INST) ? code_3inst(st) : code_1mad(st);
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) {
+            const int b = b0 + 16 * nb + row;  // batch row held by this lane
+            half4_t xb = half4_t{0, 0, 0, 0};
+            if (b < B) xb = *reinterpret_cast<const half4_t *>(X + (size_t)b * n + 16 * J + 4 * kq);
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, xb, acc[nb], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) s_part[wave][nb][r][lane] = acc[nb][r];
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) {
+            const int b = b0 + 16 * nb + row;
+            if (b >= B) continue;
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                float s = 0.f;
+#pragma unroll
+                for (int wv = 0; wv < NW; wv++) s += s_part[wv][nb][r][lane];
+                const int orow = 16 * I + 4 * kq + r;
+                if (scale) s *= (float)scale[orow];
+                Y[(size_t)b * m + orow] = s;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+
+template <int K, int V, int CODE>
+static hipError_t launch_dequantize_t(const uint32_t *codes, const uint32_t *lut, int m, int n,
+                                      void *W, hipStream_t st) {
+    const long ntiles = (long)(m / 16) * (n / 16);
+    constexpr int TPW = 64 / Geo<K>::LPT;
+    const long waves = (ntiles + TPW - 1) / TPW;
+    const long blocks = (waves + 3) / 4;
+    hipLaunchKernelGGL((dequantize_kernel<K, V, CODE>), dim3((unsigned)blocks), dim3(256), 0, st,
+                       codes, lut, n / 16, ntiles, (half_t *)W);
+    return hipGetLastError();
+}
+
+template <int K, int V, int CODE>
+static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, int m, int n,
+                                  const void *x, const void *scale, float *y, hipStream_t st) {
+    constexpr int NW = 8;
+    hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW>), dim3(m / 16), dim3(NW * 64), 0, st, codes,
+                       lut, n / 16, (const half_t *)x, (const half_t *)scale, y);
+    return hipGetLastError();
+}
+
+template <int K, int V, int CODE>
+static hipError_t launch_matmat_t(const uint32_t *codes, const uint32_t *lut, int m, int n,
+                                  const void *X, int B, const void *scale, float *Y,
+                                  hipStream_t st) {
+    constexpr int NW = 4;
+    const int groups = (B + 15) / 16;
+    if (groups == 1) {
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW>), dim3(m / 16, 1), dim3(NW * 64), 0,
+                           st, codes, lut, n / 16, m, (const half_t *)X, B,
+                           (const half_t *)scale, Y);
+    } else if (groups == 2) {
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 2, NW>), dim3(m / 16, 1), dim3(NW * 64), 0,
+                           st, codes, lut, n / 16, m, (const half_t *)X, B,
+                           (const half_t *)scale, Y);
+    } else {
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 4, NW>), dim3(m / 16, (groups + 3) / 4),
+                           dim3(NW * 64), 0, st, codes, lut, n / 16, m, (const half_t *)X, B,
+                           (const half_t *)scale, Y);
+    }
+    return hipGetLastError();
+}
+
+#define QTIP_DISPATCH(FN, ...)                                                         \
+    do {                                                                               \
+        if (code_id == CODE_HYB) {                                                     \
+            if (k == 2) return FN<2, 2, CODE_HYB>(__VA_ARGS__);                        \
+            if (k == 3) return FN<3, 2, CODE_HYB>(__VA_ARGS__);                        \
+            return FN<4, 2, CODE_HYB>(__VA_ARGS__);                                    \
+        } else if (code_id == CODE_3INST) {                                            \
+            if (k == 2) return FN<2, 1, CODE_3INST>(__VA_ARGS__);                      \
+            if (k == 3) return FN<3, 1, CODE_3INST>(__VA_ARGS__);                      \
+            return FN<4, 1, CODE_3INST>(__VA_ARGS__);                                  \
+        } else {                                                                       \
+            if (k == 2) return FN<2, 1, CODE_1MAD>(__VA_ARGS__);                       \
+            if (k == 3) return FN<3, 1, CODE_1MAD>(__VA_ARGS__);                       \
+            return FN<4, 1, CODE_1MAD>(__VA_ARGS__);                                   \
+        }                                                                              \
+    } while (0)
+
+hipError_t launch_dequantize(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                             int n, void *W, hipStream_t st) {
+    QTIP_DISPATCH(launch_dequantize_t, codes, lut, m, n, W, st);
+}
+
+hipError_t launch_matvec(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                         int n, const void *x, const void *scale, float *y, hipStream_t st) {
+    QTIP_DISPATCH(launch_matvec_t, codes, lut, m, n, x, scale, y, st);
+}
+
+hipError_t launch_matmat(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                         int n, const void *X, int B, const void *scale, float *Y,
+                         hipStream_t st) {
+    QTIP_DISPATCH(launch_matmat_t, codes, lut, m, n, X, B, scale, Y, st);
+}
+
+hipError_t launch_decode_states(int code_id, const uint32_t *states, int count,
+                                const uint32_t *lut, void *out, hipStream_t st) {
+    const int blocks = (count + 255) / 256;
+    if (code_id == CODE_HYB)
+        hipLaunchKernelGGL((decode_states_kernel<CODE_HYB>), dim3(blocks), dim3(256), 0, st, states,
+                           count, lut, (half_t *)out);
+    else if (code_id == CODE_3INST)
+        hipLaunchKernelGGL((decode_states_kernel<CODE_3INST>), dim3(blocks), dim3(256), 0, st,
+                           states, count, lut, (half_t *)out);
+    else
+        hipLaunchKernelGGL((decode_states_kernel<CODE_1MAD>), dim3(blocks), dim3(256), 0, st,
+                           states, count, lut, (half_t *)out);
+    return hipGetLastError();
+}
+
+}  // namespace qtip

@@ -1,0 +1,23 @@
+// Launchers shared between the C-ABI entry points and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qtip {
+
+hipError_t launch_dequantize(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                             int n, void *W, hipStream_t st);
+hipError_t launch_matvec(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                         int n, const void *x, const void *scale, float *y, hipStream_t st);
+hipError_t launch_matmat(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                         int n, const void *X, int B, const void *scale, float *Y, hipStream_t st);
+hipError_t launch_decode_states(int code_id, const uint32_t *states, int count,
+                                const uint32_t *lut, void *out, hipStream_t st);
+hipError_t launch_rht(const void *x, bool x_is_f32, const int8_t *signs, int n, int block,
+                      int batch, int side, void *out, hipStream_t st);
+
+// Host-only tail-biting Viterbi quantizer (qtip_quantize.cpp).
+int quantize_host(const float *W, int m, int n, int k, int V, int code_id, const uint16_t *lut,
+                  uint32_t *codes_out, double *mse_out);
+
+}  // namespace qtip

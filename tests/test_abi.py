@@ -1,0 +1,106 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every
+symbol declared in include/qtip.h, and turns bad arguments into error codes before
+any GPU work is attempted."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def q():
+    import paper_2406_11235_amd as q
+    from paper_2406_11235_amd import build
+    if build.is_stale():
+        build.build()
+    q.lib()
+    return q
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "qtip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qtip_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(q):
+    names = declared_symbols()
+    assert "qtip_decode_matvec" in names and "qtip_rht" in names and len(names) >= 9
+    L = ctypes.CDLL(q.library_path())
+    for name in names:
+        assert hasattr(L, name), name
+    from paper_2406_11235_amd import binding
+    assert sorted(binding.EXPORTS) == names
+    for name in names:
+        assert hasattr(q, name), f"binding lacks {name}"
+
+
+def test_version_matches_header(q):
+    text = open(os.path.join(ROOT, "include", "qtip.h")).read()
+    assert q.qtip_version() == int(re.search(r"#define QTIP_VERSION (\d+)", text).group(1))
+
+
+def test_argument_errors_need_no_gpu(q):
+    L = q.lib()
+    buf = np.zeros(64, dtype=np.uint32)
+    p = buf.ctypes.data                     # host memory: never dereferenced on these paths
+    EINVAL, EUNSUP = -1, -2
+    cases = [
+        (L.qtip_decode_matvec(None, 16, 2, 1, 1, None, 16, 16, p, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 16, 2, 1, 1, None, 16, 16, None, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 16, 2, 1, 1, None, 24, 16, p, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 16, 2, 1, 1, None, 16, 0, p, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 14, 2, 1, 1, None, 16, 16, p, p, None), EUNSUP),
+        (L.qtip_decode_matvec(p, 16, 5, 1, 1, None, 16, 16, p, p, None), EUNSUP),
+        (L.qtip_decode_matvec(p, 16, 1, 1, 1, None, 16, 16, p, p, None), EUNSUP),
+        (L.qtip_decode_matvec(p, 16, 2, 2, 1, None, 16, 16, p, p, None), EUNSUP),
+        (L.qtip_decode_matvec(p, 16, 2, 1, 2, p, 16, 16, p, p, None), EUNSUP),
+        (L.qtip_decode_matvec(p, 16, 2, 2, 2, None, 16, 16, p, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 16, 2, 1, 7, None, 16, 16, p, p, None), EUNSUP),
+        (L.qtip_decode_matvec(p + 4, 16, 2, 1, 1, None, 16, 16, p, p, None), EINVAL),
+        (L.qtip_decode_matmat(p, 16, 2, 1, 1, None, 16, 16, p, 0, None, p, None), EINVAL),
+        (L.qtip_decode_matmat(p, 16, 2, 1, 1, None, 16, 16, p, 4, None, None, None), EINVAL),
+        (L.qtip_dequantize(p, 16, 2, 1, 1, None, 16, 16, None, None), EINVAL),
+        (L.qtip_dequantize(p, 16, 2, 1, 0, None, 16, 20, p, None), EINVAL),
+        (L.qtip_decode_states(None, 4, 16, 1, 0, None, p, None), EINVAL),
+        (L.qtip_decode_states(p, 4, 16, 2, 0, None, p, None), EUNSUP),
+        (L.qtip_decode_states(p, -1, 16, 1, 0, None, p, None), EINVAL),
+        (L.qtip_rht(None, p, 64, 64, 1, 0, p, None), EINVAL),
+        (L.qtip_rht(p, p, 64, 48, 1, 0, p, None), EINVAL),
+        (L.qtip_rht(p, p, 96, 64, 1, 0, p, None), EINVAL),
+        (L.qtip_rht(p, p, 64, 64, 0, 0, p, None), EINVAL),
+        (L.qtip_rht(p, p, 64, 64, 1, 2, p, None), EINVAL),
+        (L.qtip_rht(p, p, 8, 8, 1, 0, p, None), EINVAL),
+        (L.qtip_rht_f32(p, p, 64, 64, 1, 0, p, None), EINVAL),     # aliasing refused
+        (L.qtip_quantize(None, 16, 16, 16, 2, 1, 1, None, p, None), EINVAL),
+        (L.qtip_quantize(p, 16, 16, 16, 2, 2, 2, None, p, None), EINVAL),
+        (L.qtip_quantize(p, 16, 16, 16, 6, 1, 1, None, p, None), EUNSUP),
+        (L.qtip_quantize(p, 16, 20, 16, 2, 1, 1, None, p, None), EINVAL),
+    ]
+    for i, (rc, want) in enumerate(cases):
+        assert rc == want, (i, rc, want, q.qtip_last_error())
+    assert "multiples of 16" in q.qtip_last_error()
+    assert L.qtip_decode_states(p, 0, 16, 1, 0, None, p, None) == 0     # empty input: no launch
+
+
+def test_binding_raises_with_message(q):
+    with pytest.raises(q.QtipError) as e:
+        q.qtip_decode_matvec(None, 16, 2, 1, 1, None, 16, 16, 0, 0, stream=0)
+    assert e.value.code == -1 and "codes is NULL" in str(e.value)
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2406_11235_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2406_11235_amd" not in text and "libqtip.so" not in text, f

@@ -1,0 +1,290 @@
+"""GPU parity: every entry point of libqtip.so, called through the C ABI, against the
+CPU oracle on the same seeded inputs.
+
+Bars: decoded fp16 weights bit-exact; products within max relative error 2e-3 of
+the fp64 oracle (fp32 accumulation), measured as max|y - y*| / max|y*|; the
+Hadamard transform within fp16 rounding of the fp64 oracle.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import qtip_synth as synth
+from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 2e-3          # the stated bar for products
+OBSERVED_TOL = 1e-4     # what fp32 accumulation actually achieves, with margin
+
+
+@pytest.fixture(scope="module")
+def q():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2406_11235_amd as q
+    q.lib()
+    return q
+
+
+def dev(a):
+    import torch
+    if a is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_err(got, ref):
+    return float(np.abs(got - ref).max() / np.abs(ref).max())
+
+
+def run_dequantize(q, w, inp):
+    import torch
+    W = torch.empty((w.m, w.n), dtype=torch.float16, device="cuda")
+    q.qtip_dequantize(dev(inp.codes), w.L, w.k, w.V, w.code_id, dev(inp.lut), w.m, w.n, W)
+    torch.cuda.synchronize()
+    return W.cpu().numpy().view(np.uint16)
+
+
+def run_matmat(q, w, inp, use_matvec=False, scale=True):
+    import torch
+    Y = torch.full((w.B, w.m), float("nan"), dtype=torch.float32, device="cuda")
+    codes, lut, X = dev(inp.codes), dev(inp.lut), dev(inp.X)
+    sc = dev(inp.row_scale) if scale else None
+    if use_matvec:
+        assert w.B == 1 and sc is None
+        q.qtip_decode_matvec(codes, w.L, w.k, w.V, w.code_id, lut, w.m, w.n, X, Y)
+    else:
+        q.qtip_decode_matmat(codes, w.L, w.k, w.V, w.code_id, lut, w.m, w.n, X, w.B, sc, Y)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy().astype(np.float64)
+
+
+ALL_CODECS = [(CODE_3INST, 2, 1), (CODE_3INST, 3, 1), (CODE_3INST, 4, 1),
+              (CODE_1MAD, 2, 1), (CODE_1MAD, 3, 1), (CODE_1MAD, 4, 1),
+              (CODE_HYB, 2, 2), (CODE_HYB, 3, 2), (CODE_HYB, 4, 2)]
+
+
+def small_workload(code_id, k, V, m, n, B=1, row_scale=False, sub=0):
+    return synth.Workload(f"small_{synth.CODE_NAMES[code_id]}_k{k}_{m}x{n}_b{B}", 9,
+                          100 * code_id + 10 * k + sub, m, n, code_id, k, V, 16, 16, B=B,
+                          row_scale=row_scale)
+
+
+# ------------------------------------------------------------------ the codes
+
+@pytest.mark.parametrize("code_id,V", [(CODE_1MAD, 1), (CODE_3INST, 1), (CODE_HYB, 2)])
+def test_code_table_all_states_bit_exact(q, code_id, V):
+    import torch
+    rng = np.random.default_rng(42)
+    lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id == CODE_HYB else None
+    states = np.arange(65536, dtype=np.uint32)
+    out = torch.zeros(65536 * V, dtype=torch.float16, device="cuda")
+    q.qtip_decode_states(dev(states), 65536, 16, V, code_id, dev(lut), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16).reshape(65536, V)
+    ref = oracle.codebook(16, V, code_id, lut).astype(np.float16).view(np.uint16)
+    assert np.array_equal(got, ref)
+
+
+# ----------------------------------------------------------------- dequantize
+
+@pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
+@pytest.mark.parametrize("m,n", [(16, 16), (48, 1072), (160, 2064)])
+def test_dequantize_small_bit_exact(q, code_id, k, V, m, n):
+    w = small_workload(code_id, k, V, m, n)
+    inp = synth.make_inputs(w)
+    got = run_dequantize(q, w, inp)
+    ref = oracle.dequantize(inp.codes, 16, k, V, code_id, m, n, inp.lut)
+    assert np.array_equal(got, ref)
+
+
+def test_dequantize_special_streams(q):
+    # all-zero and all-one streams, and a single set bit that wraps around the tile end
+    for code_id, k, V in [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 4, 2)]:
+        w = small_workload(code_id, k, V, 32, 32)
+        inp = synth.make_inputs(w)
+        for fill in (0, 0xFFFFFFFF):
+            inp.codes[:] = fill
+            ref = oracle.dequantize(inp.codes, 16, k, V, code_id, 32, 32, inp.lut)
+            assert np.array_equal(run_dequantize(q, w, inp), ref)
+        inp.codes[:] = 0
+        inp.codes[:, 0] = 0x80000000     # first bit of each tile: seen by the last states
+        inp.codes[:, -1] = 1             # last bit of each tile
+        ref = oracle.dequantize(inp.codes, 16, k, V, code_id, 32, 32, inp.lut)
+        assert np.array_equal(run_dequantize(q, w, inp), ref)
+
+
+# ----------------------------------------------------------- matvec and matmat
+
+@pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
+@pytest.mark.parametrize("m,n", [(16, 16), (48, 1072), (160, 4112)])
+def test_matvec_small(q, code_id, k, V, m, n):
+    w = small_workload(code_id, k, V, m, n)
+    inp = synth.make_inputs(w)
+    Wref = oracle.dequantize(inp.codes, 16, k, V, code_id, m, n, inp.lut)
+    ref = oracle.matmat_dense(Wref, inp.X)
+    got = run_matmat(q, w, inp, use_matvec=True, scale=False)
+    err = rel_err(got, ref)
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+
+
+@pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
+@pytest.mark.parametrize("B", [1, 3, 4, 16, 17, 40, 64, 80])
+def test_matmat_small_with_row_scale(q, code_id, k, V, B):
+    m, n = 64, 1104
+    w = small_workload(code_id, k, V, m, n, B=B, row_scale=True, sub=B)
+    inp = synth.make_inputs(w)
+    Wref = oracle.dequantize(inp.codes, 16, k, V, code_id, m, n, inp.lut)
+    ref = oracle.matmat_dense(Wref, inp.X, inp.row_scale)
+    got = run_matmat(q, w, inp)
+    err = rel_err(got, ref)
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    ref_ns = oracle.matmat_dense(Wref, inp.X)
+    assert rel_err(run_matmat(q, w, inp, scale=False), ref_ns) <= OBSERVED_TOL
+
+
+FULL = ["cfg1_3inst_k2_1024x1024", "cfg2_3inst_k2_4096x4096", "cfg3_1mad_k2_14336x4096",
+        "cfg3_1mad_k3_14336x4096", "cfg3_1mad_k4_14336x4096", "cfg3_1mad_k2_4096x14336",
+        "cfg3_1mad_k3_4096x14336", "cfg3_1mad_k4_4096x14336", "cfg4_hyb_k2_8192x28672",
+        "cfg5_hyb_k4_8192x8192_b1", "cfg5_hyb_k4_8192x8192_b4", "cfg5_hyb_k4_8192x8192_b16",
+        "cfg5_hyb_k4_8192x8192_b64", "metric_3inst_k2_8192x28672"]
+
+
+def sample_rows(w, rng, count=48):
+    """A whole tile row, the first and last rows, and random rows."""
+    I = int(rng.integers(0, w.m // 16))
+    rows = set(range(16 * I, 16 * I + 16)) | {0, w.m - 1}
+    rows |= set(int(r) for r in rng.integers(0, w.m, count))
+    return np.array(sorted(rows), dtype=np.int32)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_configs(q, name):
+    """The configured shapes in the launch configuration the benchmark times."""
+    w = synth.WORKLOADS[name]
+    inp = synth.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 7)
+    rows = sample_rows(w, rng)
+    # decoded weights: sampled rows, bit-exact
+    got_W = run_dequantize(q, w, inp)
+    for i in rows[::4]:
+        ref_row = np.array([oracle.decode_element(inp.codes, 16, w.k, w.V, w.code_id, w.n, int(i),
+                                                  j, inp.lut) for j in range(0, w.n, 7)],
+                           dtype=np.uint16)
+        assert np.array_equal(got_W[i, ::7], ref_row)
+    if w.m * w.n <= 4096 * 4096:
+        ref_W = oracle.dequantize(inp.codes, 16, w.k, w.V, w.code_id, w.m, w.n, inp.lut)
+        assert np.array_equal(got_W, ref_W)
+    del got_W
+    # products: sampled outputs computed one by one by the oracle
+    ref = oracle.decode_matmat_rows(inp.codes, 16, w.k, w.V, w.code_id, w.m, w.n, inp.X, rows,
+                                    inp.lut, scale=inp.row_scale)
+    got = run_matmat(q, w, inp)
+    assert np.all(np.isfinite(got))
+    err = float(np.abs(got[:, rows] - ref).max() / np.abs(ref).max())
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    if w.B == 1 and not w.row_scale:
+        got_mv = run_matmat(q, w, inp, use_matvec=True, scale=False)
+        assert np.array_equal(got_mv, got)          # same kernel, deterministic
+
+
+# ------------------------------------------------------------------ Hadamard
+
+@pytest.mark.parametrize("block", [16, 32, 64, 256, 1024, 2048, 4096, 8192, 16384])
+@pytest.mark.parametrize("side", [0, 1])
+def test_rht_against_explicit_matrix(q, block, side):
+    import torch
+    rng = np.random.default_rng(block + side)
+    nblk = 3 if block <= 4096 else 1
+    batch = 2 if block <= 4096 else 1
+    n = block * nblk
+    x = rng.standard_normal((batch, n)).astype(np.float16)
+    s = (rng.integers(0, 2, n) * 2 - 1).astype(np.int8)
+    ref = oracle.rht(x, s, block, side)
+    out = torch.zeros((batch, n), dtype=torch.float16, device="cuda")
+    q.qtip_rht(dev(x), dev(s), n, block, batch, side, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    # one fp16 rounding of an fp32 result
+    assert np.all(np.abs(got - ref) <= 2.0 ** -11 * np.abs(ref) + 1e-5 * np.abs(ref).max())
+    # fp32 input variant, and in-place operation of the fp16 variant
+    out2 = torch.zeros((batch, n), dtype=torch.float16, device="cuda")
+    q.qtip_rht_f32(dev(x.astype(np.float32)), dev(s), n, block, batch, side, out2)
+    xin = dev(x)
+    q.qtip_rht(xin, dev(s), n, block, batch, side, xin)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out) and torch.equal(xin, out)
+
+
+def test_full_layer_composition(q):
+    """y = S_m V_m^T (scale .* (W~ (V_n S_n x))) on config 1, GPU end to end vs oracle."""
+    import torch
+    w = synth.WORKLOADS["cfg1_3inst_k2_1024x1024"]
+    inp = synth.make_inputs(w)
+    xt = torch.empty((1, w.n), dtype=torch.float16, device="cuda")
+    q.qtip_rht(dev(inp.X), dev(inp.signs_n), w.n, w.block_n, 1, 0, xt)
+    z = torch.empty((1, w.m), dtype=torch.float32, device="cuda")
+    q.qtip_decode_matmat(dev(inp.codes), 16, w.k, w.V, w.code_id, None, w.m, w.n, xt, 1,
+                         dev(inp.row_scale), z)
+    y = torch.empty((1, w.m), dtype=torch.float16, device="cuda")
+    q.qtip_rht_f32(z, dev(inp.signs_m), w.m, w.block_m, 1, 1, y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    # oracle, all in fp64 except where the method itself rounds (the fp16 activation)
+    xt_ref = oracle.rht(inp.X, inp.signs_n, w.block_n, 0)
+    Wd = oracle.dequantize(inp.codes, 16, w.k, w.V, w.code_id, w.m, w.n).view(np.float16)
+    Wd = Wd.astype(np.float64)
+    z_ref = (Wd @ xt_ref.reshape(-1)) * inp.row_scale.astype(np.float64)
+    H = oracle.hadamard(w.block_m).astype(np.float64) / np.sqrt(w.block_m)
+    y_ref = inp.signs_m * (H.T @ z_ref)
+    assert rel_err(got, y_ref.reshape(1, -1)) <= REL_TOL
+    # and the algebra of Section 2.1: the same as the dense product with
+    # W = S_m V_m^T W~ V_n S_n
+    Hn = oracle.hadamard(w.block_n).astype(np.float64) / np.sqrt(w.block_n)
+    Wfull = (inp.signs_m[:, None] * (H.T @ (inp.row_scale.astype(np.float64)[:, None] * Wd))
+             @ Hn) * inp.signs_n[None, :]
+    y_dense = Wfull @ inp.X.astype(np.float64).reshape(-1)
+    assert np.allclose(y_ref, y_dense, rtol=1e-9, atol=1e-9)
+
+
+# ---------------------------------------------------------------- error paths
+
+def test_gpu_error_codes(q):
+    import torch
+    w = small_workload(CODE_3INST, 2, 1, 32, 32)
+    inp = synth.make_inputs(w)
+    codes, x = dev(inp.codes), dev(inp.X)
+    y = torch.zeros(32, dtype=torch.float32, device="cuda")
+    with pytest.raises(q.QtipError) as e:
+        q.qtip_decode_matvec(codes, 16, 2, 1, CODE_3INST, None, 32, 24, x, y)
+    assert e.value.code == -1
+    with pytest.raises(q.QtipError) as e:
+        q.qtip_decode_matvec(codes, 12, 2, 1, CODE_3INST, None, 32, 32, x, y)
+    assert e.value.code == -2
+    with pytest.raises(q.QtipError) as e:
+        q.qtip_decode_matvec(codes, 16, 2, 2, CODE_HYB, None, 32, 32, x, y)
+    assert e.value.code == -1
+    # a misaligned code pointer is refused, not dereferenced
+    with pytest.raises(q.QtipError):
+        q.qtip_decode_matvec(codes.data_ptr() + 4, 16, 2, 1, CODE_3INST, None, 32, 32, x, y)
+    torch.cuda.synchronize()
+    q.qtip_decode_matvec(codes, 16, 2, 1, CODE_3INST, None, 32, 32, x, y)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y).all()
+
+
+def test_quantize_roundtrip_on_gpu(q):
+    """Streams made by the host quantizer decode on the GPU to what it promised."""
+    rng = np.random.default_rng(5)
+    for code_id, k, V in [(CODE_3INST, 2, 1), (CODE_HYB, 2, 2)]:
+        lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id == CODE_HYB else None
+        sd = oracle.codebook(16, V, code_id, lut).std()
+        Wsrc = (rng.standard_normal((32, 32)) * sd).astype(np.float32)
+        codes, mse = q.qtip_quantize(Wsrc, 32, 32, 16, k, V, code_id, lut)
+        w = small_workload(code_id, k, V, 32, 32)
+        inp = synth.make_inputs(w)
+        inp.codes, inp.lut = codes, lut
+        got = run_dequantize(q, w, inp).view(np.float16).astype(np.float64)
+        assert abs(((got - Wsrc) ** 2).mean() - mse) < 1e-9
+        assert mse / sd ** 2 < 0.09

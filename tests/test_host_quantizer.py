@@ -1,0 +1,50 @@
+"""The library's host quantizer (qtip_quantize) against the oracle: its streams must
+decode, under the oracle's definition of the format, to the distortion it reports,
+and that distortion must equal the oracle's own Algorithm 4 result."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import CODE_1MAD, CODE_3INST, CODE_HYB
+
+
+@pytest.fixture(scope="module")
+def q():
+    import paper_2406_11235_amd as q
+    from paper_2406_11235_amd import build
+    if build.is_stale():
+        build.build()
+    return q
+
+
+@pytest.mark.parametrize("code_id,k,V", [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_1MAD, 4, 1),
+                                          (CODE_HYB, 2, 2), (CODE_HYB, 4, 2)])
+def test_quantizer_matches_oracle_algorithm4(q, code_id, k, V):
+    rng = np.random.default_rng(100 + 10 * code_id + k)
+    lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id == CODE_HYB else None
+    C = oracle.codebook(16, V, code_id, lut)
+    sd = C.std()
+    m, n = 16, 32
+    W = (rng.standard_normal((m, n)) * sd).astype(np.float32)
+    codes, mse = q.qtip_quantize(W, m, n, 16, k, V, code_id, lut)
+    assert codes.shape == (2, 8 * k)
+    Wd = oracle.dequantize(codes, 16, k, V, code_id, m, n, lut).view(np.float16).astype(np.float64)
+    assert abs(((Wd - W) ** 2).mean() - mse) < 1e-9
+    tot = 0.0
+    for J in range(2):
+        S = W[:, 16 * J:16 * J + 16].reshape(-1).astype(np.float64)
+        d, words = oracle.tailbiting_quantize(S, 16, k, V, C)
+        tot += d
+        # equally good streams may differ in bits; the distortion may not
+        assert abs(oracle.stream_distortion(codes[J], S, 16, k, V, C) - d) < 1e-6 * max(d, 1)
+    assert abs(tot / (m * n) - mse) < 1e-6 * max(mse, 1e-3)
+
+
+def test_quantizer_recovers_decoded_weights_exactly(q):
+    rng = np.random.default_rng(8)
+    codes = rng.integers(0, 1 << 32, (1, 16), dtype=np.uint64).astype(np.uint32)
+    W = oracle.dequantize(codes, 16, 2, 1, CODE_3INST, 16, 16).view(np.float16).astype(np.float32)
+    codes2, mse = q.qtip_quantize(W, 16, 16, 16, 2, 1, CODE_3INST)
+    assert mse == 0.0
+    W2 = oracle.dequantize(codes2, 16, 2, 1, CODE_3INST, 16, 16).view(np.float16).astype(np.float32)
+    assert np.array_equal(W, W2)
