@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the QTIP inference hot path on one MI355X.
+
+Workload (the one the headline metric is quoted on): a 8192 x 28672 layer stored as
+2-bit 3INST trellis codes (L = 16, V = 1), batch 1.  One step = the whole hot path
+once: the input-side random Hadamard transform of the activation (qtip_rht) followed
+by the fused decode + matrix-vector product (qtip_decode_matvec).  All inputs are
+seeded synthetic buffers already resident in HBM.  Consecutive steps rotate over
+enough distinct copies of the code stream (>= 512 MiB in total) that the 256 MiB
+last-level cache cannot serve them: the reported rate is an HBM rate.
+
+Prints ONE JSON line.  `value` is effective GB/s on compressed-weight bytes per step;
+`roofline` is the decode + matvec kernel alone, timed with HIP events on the stream it
+is launched on; `cpu_baseline` is the CPU oracle timed on a bounded slab of the same
+workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+WORKLOAD = "metric_3inst_k2_8192x28672"
+
+# HBM bytes per launch of the decode + matvec kernel on this workload, from
+# `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this file (summaries in
+# profiles/), scaled by what the same counters read for a plain copy of known size.
+# None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all", action="store_true",
+                    help="also time every configured workload (report on stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+            "--gpus must be 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2406_11235_amd as q
+    import qtip_synth as synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    q.lib()
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def prepare(w, min_total=512 << 20):
+        inp = synth.make_inputs(w)
+        copies = max(2, -(-min_total // w.code_bytes))
+        rng = np.random.default_rng(w.seed + 1)
+        bufs = [dev(inp.codes)]
+        for _ in range(copies - 1):
+            # distinct random streams of the same shape (decode time does not depend on bits)
+            words = rng.integers(0, 1 << 32, size=inp.codes.shape, dtype=np.uint64)
+            bufs.append(dev(words.astype(np.uint32)))
+        st = dict(w=w, inp=inp, bufs=bufs, lut=dev(inp.lut), X=dev(inp.X),
+                  signs=dev(inp.signs_n), scale=dev(inp.row_scale),
+                  xt=torch.empty((w.B, w.n), dtype=torch.float16, device="cuda"),
+                  Y=torch.empty((w.B, w.m), dtype=torch.float32, device="cuda"))
+        return st
+
+    def rht(st):
+        w = st["w"]
+        q.qtip_rht(st["X"], st["signs"], w.n, w.block_n, w.B, 0, st["xt"])
+
+    def mult(st, i):
+        w = st["w"]
+        codes = st["bufs"][i % len(st["bufs"])]
+        if w.B == 1 and st["scale"] is None:
+            q.qtip_decode_matvec(codes, w.L, w.k, w.V, w.code_id, st["lut"], w.m, w.n, st["xt"],
+                                 st["Y"])
+        else:
+            q.qtip_decode_matmat(codes, w.L, w.k, w.V, w.code_id, st["lut"], w.m, w.n, st["xt"],
+                                 w.B, st["scale"], st["Y"])
+
+    def timed(fn, steps, warmup):
+        """Average ms per call of fn(i), HIP events on the launch stream."""
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return e0.elapsed_time(e1) / steps, wall
+
+    def measure(name, steps, warmup):
+        st = prepare(synth.WORKLOADS[name])
+        w = st["w"]
+
+        def step(i):
+            rht(st)
+            mult(st, i)
+
+        ms_step, wall_step = timed(step, steps, warmup)
+        rht(st)
+        ms_kernel, _ = timed(lambda i: mult(st, i), steps, warmup)
+        ms_hot, _ = timed(lambda i: mult(st, 0), steps, warmup)
+        ms_rht, _ = timed(lambda i: rht(st), steps, warmup)
+        return st, dict(ms_step=ms_step, wall_step=wall_step, ms_kernel=ms_kernel, ms_hot=ms_hot,
+                        ms_rht=ms_rht, bytes=w.code_bytes, copies=len(st["bufs"]))
+
+    st, r = measure(args.workload, args.steps, args.warmup)
+    w = st["w"]
+    gbs = lambda ms: w.code_bytes / (ms * 1e-3) / 1e9
+    log(f"[{w.name}] step {r['ms_step']*1e3:.2f} us (wall {r['wall_step']*1e3:.2f} us), "
+        f"decode+matvec kernel {r['ms_kernel']*1e3:.2f} us cold = {gbs(r['ms_kernel']):.0f} GB/s "
+        f"({gbs(r['ms_kernel'])/HBM_PEAK_GBS*100:.1f}% of 8 TB/s), {r['ms_hot']*1e3:.2f} us "
+        f"cache-resident, rht {r['ms_rht']*1e3:.2f} us, {r['copies']} rotating buffers")
+
+    # algorithmic bytes per launch: code stream + activation + output
+    alg_bytes = w.code_bytes + 2 * w.n * w.B + 4 * w.m * w.B
+    roofline = {"bound": "hbm", "kernel": "decode+matvec", "achieved": alg_bytes / (r["ms_kernel"] * 1e-3) / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": alg_bytes / (r["ms_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC_BYTES, "us_per_launch": r["ms_kernel"] * 1e3,
+                "us_per_launch_cache_resident": r["ms_hot"] * 1e3,
+                "algorithmic_bytes": alg_bytes}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = 512
+        tn = w.n // 16
+        slab = st["inp"].codes[: (rows // 16) * tn]
+        xt = st["xt"].cpu().numpy()
+        t0 = time.perf_counter()
+        Wd = oracle.dequantize(slab, w.L, w.k, w.V, w.code_id, rows, w.n, st["inp"].lut)
+        yref = oracle.matmat_dense(Wd, xt)
+        dt = time.perf_counter() - t0
+        reps = 1
+        while dt < 10.0 and reps < 64:          # extend to about 10 s of CPU work
+            t1 = time.perf_counter()
+            Wd = oracle.dequantize(slab, w.L, w.k, w.V, w.code_id, rows, w.n, st["inp"].lut)
+            yref = oracle.matmat_dense(Wd, xt)
+            dt += time.perf_counter() - t1
+            reps += 1
+        sample_bytes = rows * w.n * w.k // 8
+        mult(st, 0)
+        torch.cuda.synchronize()
+        ygpu = st["Y"].cpu().numpy()[:, :rows]
+        err = float(np.abs(ygpu - yref).max() / np.abs(yref).max())
+        cpu_baseline = {"value": sample_bytes * reps / dt / 1e9, "unit": "GB/s",
+                        "cores": oracle.threads(), "kind": "oracle",
+                        "sample": f"first {rows} of {w.m} output rows (all {w.n} inputs), "
+                                  f"oracle dequantize + fp64 matvec, {reps} repetitions, "
+                                  f"{dt:.1f} s",
+                        "us_per_matvec_extrapolated": dt / reps * (w.m / rows) * 1e6,
+                        "gpu_vs_oracle_max_rel_err": err}
+        log(f"cpu oracle: {cpu_baseline['value']:.4f} GB/s on {cpu_baseline['cores']} threads; "
+            f"GPU vs oracle on the sample: max rel err {err:.2e}")
+
+    if args.all:
+        for name in synth.WORKLOADS:
+            if name == args.workload:
+                continue
+            st2, r2 = measure(name, max(20, args.steps // 4), args.warmup)
+            w2 = st2["w"]
+            g2 = w2.code_bytes / (r2["ms_kernel"] * 1e-3) / 1e9
+            log(f"[{name}] kernel {r2['ms_kernel']*1e3:.2f} us cold ({g2:.0f} GB/s, "
+                f"{g2/HBM_PEAK_GBS*100:.1f}%), {r2['ms_hot']*1e3:.2f} us hot, rht "
+                f"{r2['ms_rht']*1e3:.2f} us, step {r2['ms_step']*1e3:.2f} us")
+            del st2
+            torch.cuda.empty_cache()
+
+    out = {
+        "metric": "batch-1 decode+matvec effective HBM GB/s on compressed-weight bytes, "
+                  "2-bit 3INST 8192x28672",
+        "value": gbs(r["ms_step"]), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": r["ms_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": w.name, "m": w.m, "n": w.n, "code": synth.CODE_NAMES[w.code_id],
+                   "L": w.L, "k": w.k, "V": w.V, "batch": w.B, "rht_block": w.block_n,
+                   "step": "qtip_rht + qtip_decode_matvec",
+                   "rotating_code_buffers": r["copies"]},
+        "us_per_matvec": r["ms_kernel"] * 1e3, "us_rht": r["ms_rht"] * 1e3,
+        "pct_of_hbm_peak": gbs(r["ms_kernel"]) / HBM_PEAK_GBS * 100,
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -38,6 +38,9 @@ def lib():
             raise FileNotFoundError(
                 f"{_LIB_PATH} is missing: run `python -m paper_2406_11235_amd.build` "
                 "(there is no CPU fallback)")
+        # torch ships its own HIP runtime; it must be the one libqtip.so binds to, or
+        # the process ends up with two runtimes and the second one sees no device.
+        import torch  # noqa: F401
         L = ctypes.CDLL(_LIB_PATH)
         c = ctypes
         vp, i32 = c.c_void_p, c.c_int
