@@ -125,9 +125,18 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
                                                          float *__restrict__ y) {
     constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
     constexpr int TPI = 64 / LPT;  // tiles per wave per iteration
-    __shared__ uint32_t s_lut[1 << HYB_Q];
+    __shared__ uint32_t s_lut[CODE == CODE_HYB ? HYB_LDS_WORDS : 1];
     __shared__ float s_part[NW][16];
-    if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
+    if constexpr (CODE == CODE_HYB) {
+        for (int i = threadIdx.x; i < (1 << HYB_Q); i += NW * 64) {
+            const uint32_t v = lut[i];
+            s_lut[i] = v;
+            s_lut[(1 << HYB_Q) + i] = (v >> 16) | (v << 16);
+        }
+        __syncthreads();
+    }
+    RowDot<K, CODE> rd;
+    rd.init(s_lut);
     const int I = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int g = lane / LPT, q = lane & (LPT - 1);
@@ -145,18 +154,12 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
         uint32_t w[WPL + 1];
         load_tile_words<K>(codes, (size_t)I * tn + Jc, lane, w);
         const uint4 *xp = reinterpret_cast<const uint4 *>(x + 16 * Jc);
-        uint4 xa = xp[0], xb = xp[1];
+        const uint4 xa = xp[0], xb = xp[1];
         if (valid) {
-            half2_t xv[8] = {as_half2(xa.x), as_half2(xa.y), as_half2(xa.z), as_half2(xa.w),
-                             as_half2(xb.x), as_half2(xb.y), as_half2(xb.z), as_half2(xb.w)};
+            uint32_t xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+            rd.prep_x(xv);
 #pragma unroll
-            for (int rr = 0; rr < RPL; rr++) {
-                half2_t h[8];
-                decode_row<K, V, CODE>(w, rr, s_lut, h);
-#pragma unroll
-                for (int c = 0; c < 8; c++)
-                    acc[rr] = __builtin_amdgcn_fdot2(h[c], xv[c], acc[rr], false);
-            }
+            for (int rr = 0; rr < RPL; rr++) rd.run(w, rr, xv, acc[rr]);
         }
     }
     // lanes with equal q hold partial sums of the same rows: add over g

@@ -1,6 +1,21 @@
 // Device-side building blocks of the QTIP decode path for gfx950 (CDNA4):
 // tile geometry, state-window extraction from packed words held in VGPRs, and
 // the state -> fp16 value codes (Algorithms 1-3 of arXiv 2406.11235).
+//
+// Two forms of every code live here.  The plain functions (code_3inst,
+// code_1mad, code_hyb) are the definitions written out; dequantize, the
+// state-table test entry and the MFMA path use them.  The RowDot structs are
+// the batch-1 hot loop: one tile row (16 weights) decoded and contracted with 16
+// activations, arranged around what the vector ALU issues fastest on this chip
+// (measured: and/or/xor/shift-right/add/v_add_f16 run at twice the rate of
+// three-operand integer ops; v_mad_u64_u32 and v_mul_lo_u32 are full rate):
+//   * two states per funnel shift: with 16-bit states, the high and low halves
+//     of a 32-bit window at a multiple of k*V bits are both states;
+//   * the LCG a*x+b (mod 2^32) is one v_mad_u64_u32 on the zero-extended state;
+//   * mask+xor is one v_bitop3_b32;
+//   * the fp16 add of the two halves writes straight into one half of a packed
+//     register (SDWA), so a v_dot2c_f32_f16 consumes two weights at once.
+// Both forms produce the same fp16 weights bit for bit.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -23,6 +38,7 @@ constexpr uint32_t INST_A = 89226354u, INST_B = 64248484u;
 constexpr uint32_t INST_MASK = 0x8FFF8FFFu;  // sign, 2 low exponent bits, mantissa; twice
 constexpr uint32_t INST_MM = 0x3B603B60u;    // fp16(0.922) = 0x3B60 in both halves
 constexpr int HYB_Q = 9;
+constexpr float MAD_INV_SCALE = 0.0067658998646820027f;  // fp32(1 / 147.8)
 
 // How one 16x16 tile (8K words) is spread over lanes: every lane holds WPL
 // consecutive words = RPL whole tile rows; LPT lanes cover a tile.
@@ -36,15 +52,26 @@ __device__ __forceinline__ half2_t as_half2(uint32_t v) {
 }
 __device__ __forceinline__ uint32_t as_u32(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
 
-// 16-bit window starting P bits into the word array w (P is a compile-time
-// constant after unrolling; words are MSB-first, so a window is a right shift
-// of one word or of a two-word funnel).
+// 32 bits starting P bits into the word array w (MSB-first words): one word or
+// a two-word funnel shift.  P is a compile-time constant after unrolling.
+template <int NW>
+__device__ __forceinline__ uint32_t window32(const uint32_t (&w)[NW], int P) {
+    const int i = P >> 5, s = P & 31;
+    if (s == 0) return w[i];
+    return __builtin_amdgcn_alignbit(w[i], w[i + 1], 32 - s);
+}
+
+// 16-bit window starting P bits into the word array w.
 template <int NW>
 __device__ __forceinline__ uint32_t window16(const uint32_t (&w)[NW], int P) {
     const int i = P >> 5, s = P & 31;
-    if (s <= 16) return (w[i] >> (16 - s)) & 0xFFFFu;
+    if (s == 0) return w[i] >> 16;
+    if (s == 16) return w[i] & 0xFFFFu;
+    if (s < 16) return (w[i] >> (16 - s)) & 0xFFFFu;
     return __builtin_amdgcn_alignbit(w[i], w[i + 1], 48 - s) & 0xFFFFu;
 }
+
+// ------------------------------------------------------------------ plain codes
 
 // Algorithm 2: LCG, mask + XOR with the packed magic constant, sum of the two
 // fp16 halves (one IEEE binary16 add).
@@ -61,16 +88,170 @@ __device__ __forceinline__ half_t code_3inst(uint32_t x) {
 __device__ __forceinline__ half_t code_1mad(uint32_t x) {
     uint32_t X = x * MAD_A + MAD_B;
     int s = (int)__builtin_amdgcn_sad_u8(X, 0u, 0u);
-    return (half_t)((float)(s - 510) * 0.0067658998646820027f);
+    return (half_t)((float)(s - 510) * MAD_INV_SCALE);
 }
 
 // Algorithm 3 with Q = 9: hash x*x + x, bits 6..14 index the table, bit 15
 // negates the second entry.  lut holds one 32-bit word per row (entry 0 in the
-// low half); `stride` words separate consecutive rows (1 = plain table).
-__device__ __forceinline__ half2_t code_hyb(uint32_t x, const uint32_t *lut, int stride = 1) {
+// low half).
+__device__ __forceinline__ half2_t code_hyb(uint32_t x, const uint32_t *lut) {
     uint32_t X = x * x + x;
-    uint32_t v = lut[((X >> (15 - HYB_Q)) & ((1u << HYB_Q) - 1u)) * stride];
+    uint32_t v = lut[(X >> (15 - HYB_Q)) & ((1u << HYB_Q) - 1u)];
     return as_half2(v ^ ((X & 0x8000u) << 16));
 }
+
+// ------------------------------------------------------------- hot-loop pieces
+
+// (a * x + b) mod 2^32 for a zero-extended 16-bit x: one full-rate instruction.
+// b64 holds b in its low word and 0 in its high word.
+__device__ __forceinline__ uint32_t lcg_mad64(uint32_t x, uint32_t a, uint64_t b64) {
+    uint64_t d, carry;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(d), "=s"(carry) : "v"(x), "s"(a), "v"(b64));
+    return (uint32_t)d;
+}
+
+// acc += (lo(y0)+hi(y0)) * lo(x) + (lo(y1)+hi(y1)) * hi(x), twice: each fp16 sum
+// is one binary16 add written into one half of a packed register, then a dot2.
+// The two pairs are interleaved so that no instruction reads a register half-
+// written by the instruction just before it (a one-cycle hazard on this ISA).
+__device__ __forceinline__ void add_halves_dot2x2(uint32_t y0, uint32_t y1, uint32_t y2, uint32_t y3,
+                                                  uint32_t xa, uint32_t xb, float &acc) {
+    uint32_t p, q;
+    asm("v_add_f16_sdwa %0, %3, %3 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %1, %5, %5 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %0, %4, %4 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %1, %6, %6 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_dot2c_f32_f16 %2, %0, %7\n\t"
+        "v_dot2c_f32_f16 %2, %1, %8"
+        : "=&v"(p), "=&v"(q), "+v"(acc)
+        : "v"(y0), "v"(y1), "v"(y2), "v"(y3), "v"(xa), "v"(xb));
+}
+
+// The 16 zero-extended states of tile row rr of this lane's words.
+template <int K, int NW>
+__device__ __forceinline__ void row_states(const uint32_t (&w)[NW], int rr, uint32_t (&st)[16]) {
+    const int P0 = rr * 16 * K;
+    if constexpr (K == 2 || K == 4) {
+        // windows 16 bits apart are 16/K weights apart: both halves of a 32-bit
+        // window are states
+        constexpr int G = 16 / K;  // weights between the two halves
+#pragma unroll
+        for (int base = 0; base < 16; base += 2 * G)
+#pragma unroll
+            for (int j = 0; j < G; j++) {
+                uint32_t R = window32(w, P0 + (base + j) * K);
+                st[base + j] = R >> 16;
+                st[base + j + G] = R & 0xFFFFu;
+            }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 16; c++) st[c] = window16(w, P0 + c * K);
+    }
+}
+
+template <int K, int CODE> struct RowDot;
+
+// 3INST, V = 1.
+template <int K> struct RowDot<K, CODE_3INST> {
+    uint64_t b64;
+    uint32_t mm;
+    __device__ __forceinline__ void init(const uint32_t *) {
+        b64 = INST_B;
+        mm = INST_MM;
+        // keep the constants in VGPRs (they feed VOP3 slots next to an SGPR)
+        asm volatile("" : "+v"(b64), "+v"(mm));
+    }
+    __device__ __forceinline__ void prep_x(uint32_t (&)[8]) const {}
+    template <int NW>
+    __device__ __forceinline__ void run(const uint32_t (&w)[NW], int rr, const uint32_t (&x)[8],
+                                        float &acc) const {
+        uint32_t st[16], y[16];
+        row_states<K>(w, rr, st);
+#pragma unroll
+        for (int c = 0; c < 16; c++) y[c] = (lcg_mad64(st[c], INST_A, b64) & INST_MASK) ^ mm;
+#pragma unroll
+        for (int c = 0; c < 16; c += 4)
+            add_halves_dot2x2(y[c], y[c + 1], y[c + 2], y[c + 3], x[c / 2], x[c / 2 + 1], acc);
+    }
+};
+
+// 1MAD, V = 1.
+template <int K> struct RowDot<K, CODE_1MAD> {
+    uint64_t b64;
+    __device__ __forceinline__ void init(const uint32_t *) {
+        b64 = MAD_B;
+        asm volatile("" : "+v"(b64));
+    }
+    __device__ __forceinline__ void prep_x(uint32_t (&)[8]) const {}
+    template <int NW>
+    __device__ __forceinline__ void run(const uint32_t (&w)[NW], int rr, const uint32_t (&x)[8],
+                                        float &acc) const {
+        uint32_t st[16];
+        row_states<K>(w, rr, st);
+#pragma unroll
+        for (int c = 0; c < 16; c += 2) {
+            float f[2];
+#pragma unroll
+            for (int e = 0; e < 2; e++) {
+                uint32_t X = lcg_mad64(st[c + e], MAD_A, b64);
+                // byte sum on top of the bits of 2^23: the result is the float 2^23 + s
+                uint32_t t = __builtin_amdgcn_sad_u8(X, 0u, 0x4B000000u);
+                f[e] = (__builtin_bit_cast(float, t) - 8389118.0f) * MAD_INV_SCALE;  // s - 510
+            }
+            half2_t h = {(half_t)f[0], (half_t)f[1]};
+            acc = __builtin_amdgcn_fdot2(h, as_half2(x[c / 2]), acc, false);
+        }
+    }
+};
+
+// HYB, V = 2: the LUT sits in LDS twice, once as stored (entry 0 low, entry 1
+// high) and once with the halves swapped, so that the sign bit of the hash lines
+// up with entry 1 whichever half of a packed register the hash sits in.
+constexpr int HYB_LDS_WORDS = 2 << HYB_Q;
+template <int K> struct RowDot<K, CODE_HYB> {
+    const uint32_t *lut;  // LDS: [0, 512) stored order, [512, 1024) halves swapped
+    __device__ __forceinline__ void init(const uint32_t *lds_lut) { lut = lds_lut; }
+    // activations that meet a swapped table entry get their halves swapped too
+    __device__ __forceinline__ void prep_x(uint32_t (&x)[8]) const {
+        if constexpr (K == 2 || K == 4) {
+            constexpr int G = 8 / K;
+#pragma unroll
+            for (int base = 0; base < 8; base += 2 * G)
+#pragma unroll
+                for (int j = 0; j < G; j++)
+                    x[base + j + G] = __builtin_amdgcn_alignbit(x[base + j + G], x[base + j + G], 16);
+        }
+    }
+    template <int NW>
+    __device__ __forceinline__ void run(const uint32_t (&w)[NW], int rr, const uint32_t (&x)[8],
+                                        float &acc) const {
+        const int P0 = rr * 16 * K;
+        if constexpr (K == 2 || K == 4) {
+            constexpr int G = 8 / K;  // states between the two halves of a window
+#pragma unroll
+            for (int base = 0; base < 8; base += 2 * G)
+#pragma unroll
+                for (int j = 0; j < G; j++) {
+                    uint32_t R = window32(w, P0 + (base + j) * 2 * K);
+                    // both hashes at once: low 16 bits of x*x + x in each half
+                    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+                    us2 r2 = __builtin_bit_cast(us2, R);
+                    uint32_t H = __builtin_bit_cast(uint32_t, (us2)(r2 * r2 + r2));
+                    // high half = state base+j: stored-order table, sign at bit 31
+                    uint32_t vh = lut[(H >> 22) & 0x1FFu] ^ (H & 0x80000000u);
+                    // low half = state base+j+G: swapped table, sign at bit 15
+                    uint32_t vl = lut[512 + ((H >> 6) & 0x1FFu)] ^ (H & 0x8000u);
+                    acc = __builtin_amdgcn_fdot2(as_half2(vh), as_half2(x[base + j]), acc, false);
+                    acc = __builtin_amdgcn_fdot2(as_half2(vl), as_half2(x[base + j + G]), acc, false);
+                }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 8; c++) {
+                half2_t v = code_hyb(window16(w, P0 + c * 2 * K), lut);
+                acc = __builtin_amdgcn_fdot2(v, as_half2(x[c]), acc, false);
+            }
+        }
+    }
+};
 
 }  // namespace qtip
