@@ -74,7 +74,8 @@ extern "C" {
  * x: device, batch x n row-major, fp16 (qtip_rht) or fp32 (qtip_rht_f32, for
  * feeding the fp32 result of a multiply straight into the output-side transform).
  * signs: device, n int8 values, each +1 or -1.  out_f16: device, batch x n fp16.
- * out may alias x in qtip_rht.  Arithmetic is fp32, rounded once to fp16.
+ * out may alias x in qtip_rht.  x, signs and out must be 16-byte aligned.
+ * Arithmetic is fp32, rounded once to fp16.
  */
 int qtip_rht(const void *x_f16, const int8_t *signs, int n, int block, int batch, int side,
              void *out_f16, void *stream);

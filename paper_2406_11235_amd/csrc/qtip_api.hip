@@ -52,6 +52,8 @@ int rht_common(const char *fn, const void *x, bool f32, const int8_t *signs, int
     if (n <= 0 || n % block) return fail(QTIP_EINVAL, "%s: n = %d is not a multiple of block %d", fn, n, block);
     if (batch < 1 || batch > 65535) return fail(QTIP_EINVAL, "%s: batch = %d out of range", fn, batch);
     if (side != 0 && side != 1) return fail(QTIP_EINVAL, "%s: side = %d must be 0 or 1", fn, side);
+    if (!aligned(x, 16) || !aligned(signs, 16) || !aligned(out, 16))
+        return fail(QTIP_EINVAL, "%s: x, signs and out must be 16-byte aligned", fn);
     hipError_t e = qtip::launch_rht(x, f32, signs, n, block, batch, side, out, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(fn, e);
     return QTIP_OK;

@@ -16,20 +16,32 @@ template <> struct Words<2> { uint32_t v[4]; };
 template <> struct Words<3> { uint32_t v[3]; };
 template <> struct Words<4> { uint32_t v[4]; };
 
-// Load this lane's WPL words of tile `tile` plus the first word of the next
-// lane of the same tile (cyclically: the tail-biting wrap of Section 3.2).
+// This lane's WPL words of tile `tile` (q = lane's position inside the tile).
+template <int K>
+__device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ codes, size_t tile,
+                                               int q) {
+    constexpr int WPL = Geo<K>::WPL;
+    const uint32_t *p = codes + tile * (8 * K) + q * WPL;
+    Words<K> r;
+    if constexpr (WPL == 4) {
+        const uint4 t = *reinterpret_cast<const uint4 *>(p);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+        r.v[0] = p[0]; r.v[1] = p[1]; r.v[2] = p[2];
+    }
+    return r;
+}
+
+// The same plus the first word of the next lane of the same tile (cyclically: the
+// tail-biting wrap of Section 3.2).
 template <int K>
 __device__ __forceinline__ void load_tile_words(const uint32_t *__restrict__ codes, size_t tile,
                                                 int lane, uint32_t (&w)[Geo<K>::WPL + 1]) {
     constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT;
     const int q = lane & (LPT - 1);
-    const uint32_t *p = codes + tile * (8 * K) + q * WPL;
-    if constexpr (WPL == 4) {
-        uint4 t = *reinterpret_cast<const uint4 *>(p);
-        w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
-    } else {
-        w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
-    }
+    const Words<K> r = load_words<K>(codes, tile, q);
+#pragma unroll
+    for (int i = 0; i < WPL; i++) w[i] = r.v[i];
     w[WPL] = __shfl(w[0], (lane & ~(LPT - 1)) | ((q + 1) & (LPT - 1)), 64);
 }
 
@@ -147,15 +159,27 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
 #pragma unroll
     for (int rr = 0; rr < RPL; rr++) acc[rr] = 0.f;
 
-    for (int Jb = J0; Jb < Jend; Jb += TPI) {
-        const int J = Jb + g;
-        const bool valid = J < Jend;
-        const int Jc = valid ? J : Jend - 1;
-        uint32_t w[WPL + 1];
-        load_tile_words<K>(codes, (size_t)I * tn + Jc, lane, w);
+    // Software pipeline: the loads of step i+1 are in flight while step i is decoded.
+    Words<K> wn;
+    uint4 xan, xbn;
+    auto issue = [&](int Jb) {
+        const int Jc = min(Jb + g, Jend - 1);  // lanes past the end re-read the last tile
+        wn = load_words<K>(codes, (size_t)I * tn + Jc, q);
         const uint4 *xp = reinterpret_cast<const uint4 *>(x + 16 * Jc);
-        const uint4 xa = xp[0], xb = xp[1];
-        if (valid) {
+        xan = xp[0];
+        xbn = xp[1];
+    };
+    if (J0 < Jend) issue(J0);
+    for (int Jb = J0; Jb < Jend; Jb += TPI) {
+        const Words<K> wc = wn;
+        const uint4 xa = xan, xb = xbn;
+        if (Jb + TPI < Jend) issue(Jb + TPI);
+        uint32_t w[WPL + 1];
+#pragma unroll
+        for (int i = 0; i < WPL; i++) w[i] = wc.v[i];
+        // first word of the next lane of the same tile, cyclically (tail-biting wrap)
+        w[WPL] = __shfl(w[0], (lane & ~(LPT - 1)) | ((q + 1) & (LPT - 1)), 64);
+        if (Jb + g < Jend) {
             uint32_t xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
             rd.prep_x(xv);
 #pragma unroll
