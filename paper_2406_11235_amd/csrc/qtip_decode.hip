@@ -182,8 +182,7 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
         if (Jb + g < Jend) {
             uint32_t xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
             rd.prep_x(xv);
-#pragma unroll
-            for (int rr = 0; rr < RPL; rr++) rd.run(w, rr, xv, acc[rr]);
+            rd.run_tile(w, xv, acc);
         }
     }
     // lanes with equal q hold partial sums of the same rows: add over g

@@ -173,6 +173,12 @@ template <int K> struct RowDot<K, CODE_3INST> {
         for (int c = 0; c < 16; c += 4)
             add_halves_dot2x2(y[c], y[c + 1], y[c + 2], y[c + 3], x[c / 2], x[c / 2 + 1], acc);
     }
+    template <int NW, int RPL>
+    __device__ __forceinline__ void run_tile(const uint32_t (&w)[NW], const uint32_t (&x)[8],
+                                             float (&acc)[RPL]) const {
+#pragma unroll
+        for (int rr = 0; rr < RPL; rr++) run(w, rr, x, acc[rr]);
+    }
 };
 
 // 1MAD, V = 1.
@@ -202,6 +208,12 @@ template <int K> struct RowDot<K, CODE_1MAD> {
             acc = __builtin_amdgcn_fdot2(h, as_half2(x[c / 2]), acc, false);
         }
     }
+    template <int NW, int RPL>
+    __device__ __forceinline__ void run_tile(const uint32_t (&w)[NW], const uint32_t (&x)[8],
+                                             float (&acc)[RPL]) const {
+#pragma unroll
+        for (int rr = 0; rr < RPL; rr++) run(w, rr, x, acc[rr]);
+    }
 };
 
 // HYB, V = 2: the LUT sits in LDS twice, once as stored (entry 0 low, entry 1
@@ -222,34 +234,59 @@ template <int K> struct RowDot<K, CODE_HYB> {
                     x[base + j + G] = __builtin_amdgcn_alignbit(x[base + j + G], x[base + j + G], 16);
         }
     }
-    template <int NW>
-    __device__ __forceinline__ void run(const uint32_t (&w)[NW], int rr, const uint32_t (&x)[8],
-                                        float &acc) const {
-        const int P0 = rr * 16 * K;
+    // All RPL rows of this lane, software-pipelined by row: the hashes and the eight
+    // table reads of row r+1 are issued before the reads of row r are consumed, so
+    // a wave keeps the LDS and the vector ALU busy at the same time by itself.
+    // (Waves of a workgroup run in near lockstep; leaving the overlap to chance
+    // between waves makes LDS time and ALU time add up instead.)
+    template <int NW, int RPL>
+    __device__ __forceinline__ void run_tile(const uint32_t (&w)[NW], const uint32_t (&x)[8],
+                                             float (&acc)[RPL]) const {
         if constexpr (K == 2 || K == 4) {
             constexpr int G = 8 / K;  // states between the two halves of a window
+            uint32_t H[RPL][4], v[RPL][8];
+            auto issue_row = [&](int rr) {
 #pragma unroll
-            for (int base = 0; base < 8; base += 2 * G)
+                for (int base = 0, i = 0; base < 8; base += 2 * G)
 #pragma unroll
-                for (int j = 0; j < G; j++) {
-                    uint32_t R = window32(w, P0 + (base + j) * 2 * K);
-                    // both hashes at once: low 16 bits of x*x + x in each half
-                    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-                    us2 r2 = __builtin_bit_cast(us2, R);
-                    uint32_t H = __builtin_bit_cast(uint32_t, (us2)(r2 * r2 + r2));
-                    // high half = state base+j: stored-order table, sign at bit 31
-                    uint32_t vh = lut[(H >> 22) & 0x1FFu] ^ (H & 0x80000000u);
-                    // low half = state base+j+G: swapped table, sign at bit 15
-                    uint32_t vl = lut[512 + ((H >> 6) & 0x1FFu)] ^ (H & 0x8000u);
-                    acc = __builtin_amdgcn_fdot2(as_half2(vh), as_half2(x[base + j]), acc, false);
-                    acc = __builtin_amdgcn_fdot2(as_half2(vl), as_half2(x[base + j + G]), acc, false);
+                    for (int j = 0; j < G; j++, i++) {
+                        uint32_t R = window32(w, rr * 16 * K + (base + j) * 2 * K);
+                        // both hashes at once: low 16 bits of x*x + x in each half
+                        typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+                        us2 r2 = __builtin_bit_cast(us2, R);
+                        H[rr][i] = __builtin_bit_cast(uint32_t, (us2)(r2 * r2 + r2));
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    v[rr][2 * i] = lut[(H[rr][i] >> 22) & 0x1FFu];             // high: stored order
+                    v[rr][2 * i + 1] = lut[512 + ((H[rr][i] >> 6) & 0x1FFu)];  // low: swapped
                 }
+            };
+            issue_row(0);
+#pragma unroll
+            for (int rr = 0; rr < RPL; rr++) {
+                if (rr + 1 < RPL) issue_row(rr + 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int base = 0, i = 0; base < 8; base += 2 * G)
+#pragma unroll
+                    for (int j = 0; j < G; j++, i++) {
+                        // sign of the hash: bit 31 for the high half, bit 15 for the low half
+                        uint32_t vh = v[rr][2 * i] ^ (H[rr][i] & 0x80000000u);
+                        uint32_t vl = v[rr][2 * i + 1] ^ (H[rr][i] & 0x8000u);
+                        acc[rr] = __builtin_amdgcn_fdot2(as_half2(vh), as_half2(x[base + j]), acc[rr], false);
+                        acc[rr] = __builtin_amdgcn_fdot2(as_half2(vl), as_half2(x[base + j + G]), acc[rr], false);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         } else {
 #pragma unroll
-            for (int c = 0; c < 8; c++) {
-                half2_t v = code_hyb(window16(w, P0 + c * 2 * K), lut);
-                acc = __builtin_amdgcn_fdot2(v, as_half2(x[c]), acc, false);
-            }
+            for (int rr = 0; rr < RPL; rr++)
+#pragma unroll
+                for (int c = 0; c < 8; c++) {
+                    half2_t hv = code_hyb(window16(w, rr * 16 * K + c * 2 * K), lut);
+                    acc[rr] = __builtin_amdgcn_fdot2(hv, as_half2(x[c]), acc[rr], false);
+                }
         }
     }
 };
