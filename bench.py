@@ -45,6 +45,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy five times, so that a rocprofv3 "
+                         "--pmc FETCH_SIZE / WRITE_SIZE run of this file has a kernel of known "
+                         "traffic to scale the counters by")
     ap.add_argument("--all", action="store_true",
                     help="also time every configured workload (report on stderr)")
     args = ap.parse_args()
@@ -204,6 +208,14 @@ def main():
                         "gpu_vs_oracle_max_rel_err": err}
         log(f"cpu oracle: {cpu_baseline['value']:.4f} GB/s on {cpu_baseline['cores']} threads; "
             f"GPU vs oracle on the sample: max rel err {err:.2e}")
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if args.all:
         for name in synth.WORKLOADS:

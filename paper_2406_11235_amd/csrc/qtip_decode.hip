@@ -46,8 +46,8 @@ __device__ __forceinline__ void load_tile_words(const uint32_t *__restrict__ cod
 }
 
 // Decode tile row rr (0..RPL-1) of this lane: 16 fp16 weights as 8 pairs.
-template <int K, int V, int CODE>
-__device__ __forceinline__ void decode_row(const uint32_t (&w)[Geo<K>::WPL + 1], int rr,
+template <int K, int V, int CODE, int NWD>
+__device__ __forceinline__ void decode_row(const uint32_t (&w)[NWD], int rr,
                                            const uint32_t *lut, half2_t (&out)[8]) {
 #pragma unroll
     for (int c = 0; c < 8; c++) {
@@ -207,83 +207,160 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
 
 // ------------------------------------------- decode + batched product on MFMA
 //
-// Per tile one v_mfma_f32_16x16x16_f16 per group of 16 batch rows:
-//   A (16 x 16, rows = tile rows, cols = tile columns): lane l holds
-//       A[l % 16][4*(l/16) .. 4*(l/16)+3] = four consecutive sequence elements,
-//       which is what a lane decodes from a 16 + 3k-bit window;
-//   B (16 x 16, rows = tile columns, cols = batch): lane l holds
-//       X[b0 + l % 16][16J + 4*(l/16) .. +3];
-//   D (rows = tile rows, cols = batch): lane l holds D[4*(l/16) + r][l % 16].
+// v_mfma_f32_16x16x32_f16, D = A * B, with the decoded weights as A and the
+// activations as B.  A wave step covers four tiles (I, J0..J0+3) of one tile row:
+//   lane l = (row i = l % 16, slot s = l / 16) decodes the whole tile row i of tile
+//   J0 + s: 16 weights = 8 packed registers, the A operands of two MFMAs (columns
+//   0..7 and 8..15 of the tile);
+//   the matching B operand of lane (j = l % 16, s) is X[b0 + j][16 (J0+s) + 8h .. +7],
+//   one 16-byte load; A and B pair contraction slots by (s, element), so the order
+//   in which the hardware numbers them does not matter;
+//   D[4 (l / 16) + r][l % 16] = output row 16 I + 4 (l/16) + r for batch row b0 + l % 16.
+// A wave owns R = 2 neighbouring tile rows so that every B operand it loads feeds
+// two MFMAs; NB groups of 16 batch rows share every decoded weight.  The waves of
+// a workgroup split the tiles of the row band and meet in LDS.
+
+// The words that hold tile row i (16 K bits from bit 16 K i) and the 16 - K V bits
+// after it, brought to bit offset 0; indices wrap inside the tile (tail-biting).
+template <int K>
+__device__ __forceinline__ void load_row_words(const uint32_t *__restrict__ tile, int i,
+                                               uint32_t (&w)[3]) {
+    constexpr int NWORDS = 8 * K;
+    const int bit = 16 * K * i;
+    const int w0 = bit >> 5;
+    w[0] = tile[w0];
+    w[1] = tile[(w0 + 1) % NWORDS];
+    w[2] = (K == 2) ? 0u : tile[(w0 + 2) % NWORDS];
+}
+template <int K>
+__device__ __forceinline__ void align_row_words(int i, uint32_t (&w)[3]) {
+    if constexpr (K == 3) {
+        if (i & 1) {  // odd rows start in the middle of a word
+            w[0] = __builtin_amdgcn_alignbit(w[0], w[1], 16);
+            w[1] = __builtin_amdgcn_alignbit(w[1], w[2], 16);
+            w[2] <<= 16;
+        }
+    }
+}
+
+template <int K, int V, int CODE>
+__device__ __forceinline__ half8_t pack8(const half2_t (&h)[8], int half) {
+    half8_t a;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        a[2 * e] = h[4 * half + e].x;
+        a[2 * e + 1] = h[4 * half + e].y;
+    }
+    return a;
+}
 
 template <int K, int V, int CODE, int NB, int NW>
 __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
-                                                         int tn, int m, const half_t *__restrict__ X,
+                                                         int tm, int tn, const half_t *__restrict__ X,
                                                          int B, const half_t *__restrict__ scale,
                                                          float *__restrict__ Y) {
+    constexpr int R = 2;
+    constexpr int NWORDS = 8 * K;
     __shared__ uint32_t s_lut[1 << HYB_Q];
-    __shared__ float s_part[NW][NB][4][64];
+    __shared__ float s_part[NW - 1][R][NB][4][64];
     if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
-    const int I = blockIdx.x;
+    const int I0 = blockIdx.x * R;
     const int b0 = blockIdx.y * (16 * NB);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int row = lane & 15, kq = lane >> 4;
+    const int i = lane & 15, s = lane >> 4;
     const size_t n = (size_t)tn * 16;
-    const int chunk = (tn + NW - 1) / NW;
+    const int m = tm * 16;
+    const int chunk = ((tn + NW * 4 - 1) / (NW * 4)) * 4;
     const int J0 = wave * chunk;
     const int Jend = min(tn, J0 + chunk);
-    float4_t acc[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; nb++) acc[nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    const bool row_ok[R] = {true, I0 + 1 < tm};
 
-    // this lane's four weights start P bits into the tile
-    const int P = (16 * row + 4 * kq) * K;
-    const int wi = P >> 5, sh = P & 31;
-    constexpr int NWORDS = 8 * K;
-    for (int J = J0; J < Jend; J++) {
-        const uint32_t *tp = codes + ((size_t)I * tn + J) * NWORDS;
-        // 16 + 3K (V = 1) or 16 + KV (V = 2) bits from offset sh of a 64-bit funnel
-        uint32_t w0 = tp[wi], w1 = tp[(wi + 1) % NWORDS];
-        uint64_t f = ((uint64_t)w0 << 32) | w1;
-        half4_t a;
-        if constexpr (V == 2) {
-            uint32_t s0 = (uint32_t)(f >> (48 - sh)) & 0xFFFFu;
-            uint32_t s1 = (uint32_t)(f >> (48 - sh - 2 * K)) & 0xFFFFu;
-            half2_t h0 = code_hyb(s0, s_lut), h1 = code_hyb(s1, s_lut);
-            a = half4_t{h0.x, h0.y, h1.x, h1.y};
-        } else {
+    float4_t acc[R][NB];
 #pragma unroll
-            for (int e = 0; e < 4; e++) {
-                uint32_t st = (uint32_t)(f >> (48 - sh - e * K)) & 0xFFFFu;
-                a[e] = (CODE == CODE_3INST) ? code_3inst(st) : code_1mad(st);
-            }
+    for (int r = 0; r < R; r++)
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) acc[r][nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // software pipeline: operands of step t+1 are loaded while step t runs
+    uint32_t wn[R][3];
+    half8_t xn[NB][2];
+    auto issue = [&](int Jb) {
+        const int J = min(Jb + s, Jend - 1);  // slots past the end re-read the last tile
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            const int I = row_ok[r] ? I0 + r : I0;
+            load_row_words<K>(codes + ((size_t)I * tn + J) * NWORDS, i, wn[r]);
         }
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) {
-            const int b = b0 + 16 * nb + row;  // batch row held by this lane
-            half4_t xb = half4_t{0, 0, 0, 0};
-            if (b < B) xb = *reinterpret_cast<const half4_t *>(X + (size_t)b * n + 16 * J + 4 * kq);
-            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, xb, acc[nb], 0, 0, 0);
+            const int b = b0 + 16 * nb + i;
+            const half_t *xp = X + (size_t)min(b, B - 1) * n + 16 * J;
+            xn[nb][0] = *reinterpret_cast<const half8_t *>(xp);
+            xn[nb][1] = *reinterpret_cast<const half8_t *>(xp + 8);
+        }
+    };
+    if (J0 < Jend) issue(J0);
+    for (int Jb = J0; Jb < Jend; Jb += 4) {
+        uint32_t w[R][3];
+        half8_t xb[NB][2];
+#pragma unroll
+        for (int r = 0; r < R; r++)
+#pragma unroll
+            for (int t = 0; t < 3; t++) w[r][t] = wn[r][t];
+        const bool live = Jb + s < Jend;
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) {
+            const bool bok = live && (b0 + 16 * nb + i < B);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                xb[nb][h] = xn[nb][h];
+                if (!bok) xb[nb][h] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};  // dead slot / batch row
+            }
+        }
+        if (Jb + 4 < Jend) issue(Jb + 4);
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            align_row_words<K>(i, w[r]);
+            half2_t hrow[8];
+            decode_row<K, V, CODE>(w[r], 0, s_lut, hrow);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const half8_t a = pack8<K, V, CODE>(hrow, h);
+#pragma unroll
+                for (int nb = 0; nb < NB; nb++)
+                    acc[r][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xb[nb][h], acc[r][nb], 0, 0, 0);
+            }
         }
     }
+    if (wave > 0) {
 #pragma unroll
-    for (int nb = 0; nb < NB; nb++)
+        for (int r = 0; r < R; r++)
 #pragma unroll
-        for (int r = 0; r < 4; r++) s_part[wave][nb][r][lane] = acc[nb][r];
+            for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+                for (int e = 0; e < 4; e++) s_part[wave - 1][r][nb][e][lane] = acc[r][nb][e];
+    }
     __syncthreads();
     if (wave == 0) {
 #pragma unroll
-        for (int nb = 0; nb < NB; nb++) {
-            const int b = b0 + 16 * nb + row;
-            if (b >= B) continue;
+        for (int r = 0; r < R; r++) {
+            if (!row_ok[r]) continue;
 #pragma unroll
-            for (int r = 0; r < 4; r++) {
-                float s = 0.f;
+            for (int nb = 0; nb < NB; nb++) {
+                const int b = b0 + 16 * nb + i;
+                if (b >= B) continue;
+                float4_t v = acc[r][nb];
 #pragma unroll
-                for (int wv = 0; wv < NW; wv++) s += s_part[wv][nb][r][lane];
-                const int orow = 16 * I + 4 * kq + r;
-                if (scale) s *= (float)scale[orow];
-                Y[(size_t)b * m + orow] = s;
+                for (int wv = 0; wv < NW - 1; wv++)
+#pragma unroll
+                    for (int e = 0; e < 4; e++) v[e] += s_part[wv][r][nb][e][lane];
+                const int orow = 16 * (I0 + r) + 4 * s;
+                if (scale) {
+#pragma unroll
+                    for (int e = 0; e < 4; e++) v[e] *= (float)scale[orow + e];
+                }
+                *reinterpret_cast<float4_t *>(Y + (size_t)b * m + orow) = v;
             }
         }
     }
@@ -316,19 +393,19 @@ template <int K, int V, int CODE>
 static hipError_t launch_matmat_t(const uint32_t *codes, const uint32_t *lut, int m, int n,
                                   const void *X, int B, const void *scale, float *Y,
                                   hipStream_t st) {
-    constexpr int NW = 4;
+    constexpr int NW = 8;
     const int groups = (B + 15) / 16;
+    const int tm = m / 16, tn = n / 16;
+    const dim3 block(NW * 64);
     if (groups == 1) {
-        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW>), dim3(m / 16, 1), dim3(NW * 64), 0,
-                           st, codes, lut, n / 16, m, (const half_t *)X, B,
-                           (const half_t *)scale, Y);
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW>), dim3((tm + 1) / 2, 1), block, 0, st,
+                           codes, lut, tm, tn, (const half_t *)X, B, (const half_t *)scale, Y);
     } else if (groups == 2) {
-        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 2, NW>), dim3(m / 16, 1), dim3(NW * 64), 0,
-                           st, codes, lut, n / 16, m, (const half_t *)X, B,
-                           (const half_t *)scale, Y);
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 2, NW>), dim3((tm + 1) / 2, 1), block, 0, st,
+                           codes, lut, tm, tn, (const half_t *)X, B, (const half_t *)scale, Y);
     } else {
-        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 4, NW>), dim3(m / 16, (groups + 3) / 4),
-                           dim3(NW * 64), 0, st, codes, lut, n / 16, m, (const half_t *)X, B,
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 4, NW>), dim3((tm + 1) / 2, (groups + 3) / 4),
+                           block, 0, st, codes, lut, tm, tn, (const half_t *)X, B,
                            (const half_t *)scale, Y);
     }
     return hipGetLastError();
