@@ -252,9 +252,7 @@ template <int K> struct RowDot<K, CODE_HYB> {
                     for (int j = 0; j < G; j++, i++) {
                         uint32_t R = window32(w, rr * 16 * K + (base + j) * 2 * K);
                         // both hashes at once: low 16 bits of x*x + x in each half
-                        typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-                        us2 r2 = __builtin_bit_cast(us2, R);
-                        H[rr][i] = __builtin_bit_cast(uint32_t, (us2)(r2 * r2 + r2));
+                        asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H[rr][i]) : "v"(R));
                     }
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
