@@ -30,8 +30,9 @@ WORKLOAD = "metric_3inst_k2_8192x28672"
 # HBM bytes per launch of the decode + matvec kernel on this workload, from
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this file (summaries in
 # profiles/), scaled by what the same counters read for a plain copy of known size.
-# None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# profiles/matvec_3inst_k2_8192x28672_traffic.txt: FETCH_SIZE 28944.1 KiB x 1.9998 (the copy kernel reads
+# half of what it moves on this counter) + WRITE_SIZE 32.0 KiB x 1.0000.
+MEASURED_TRAFFIC_BYTES = {"metric_3inst_k2_8192x28672": 59304557}
 
 
 def log(*a):
@@ -172,7 +173,7 @@ def main():
     roofline = {"bound": "hbm", "kernel": "decode+matvec", "achieved": alg_bytes / (r["ms_kernel"] * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": alg_bytes / (r["ms_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES, "us_per_launch": r["ms_kernel"] * 1e3,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "us_per_launch": r["ms_kernel"] * 1e3,
                 "us_per_launch_cache_resident": r["ms_hot"] * 1e3,
                 "algorithmic_bytes": alg_bytes}
 
