@@ -9,6 +9,8 @@
 #include "qtip_device.h"
 #include "qtip_internal.h"
 
+#include <cstdlib>
+
 namespace qtip {
 
 template <int K> struct Words;
@@ -380,12 +382,41 @@ static hipError_t launch_dequantize_t(const uint32_t *codes, const uint32_t *lut
     return hipGetLastError();
 }
 
+// Waves per workgroup for the batch-1 kernel.  A workgroup owns one tile row, so the
+// grid has m/16 workgroups and NW decides both how many waves the chip gets and how
+// many steps each wave runs: few steps leave a wave's start-up and reduction exposed,
+// few waves leave SIMDs idle or the vector ALU short of waves to interleave.
+static int pick_matvec_waves(int tm, int steps_per_row) {
+    static const char *env = getenv("QTIP_MATVEC_WAVES");  // tuning override: 2, 4, 8 or 16
+    if (env) {
+        const int v = atoi(env);
+        if (v == 2 || v == 4 || v == 8 || v == 16) return v;
+    }
+    (void)tm;
+    // measured on the configured shapes: occupancy matters more than steps per wave;
+    // 16 waves win once a wave still gets 4 steps, 8 are best for mid-sized rows
+    if (steps_per_row >= 64) return 16;
+    if (steps_per_row >= 8) return 8;
+    if (steps_per_row >= 4) return 4;
+    return 2;
+}
+
 template <int K, int V, int CODE>
 static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, int m, int n,
                                   const void *x, const void *scale, float *y, hipStream_t st) {
-    constexpr int NW = 8;
-    hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW>), dim3(m / 16), dim3(NW * 64), 0, st, codes,
-                       lut, n / 16, (const half_t *)x, (const half_t *)scale, y);
+    constexpr int TPI = 64 / Geo<K>::LPT;
+    const int tm = m / 16, tn = n / 16;
+    const int nw = pick_matvec_waves(tm, (tn + TPI - 1) / TPI);
+#define QTIP_MV_LAUNCH(NW)                                                                        \
+    hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW>), dim3(tm), dim3(NW * 64), 0, st, codes, lut, \
+                       tn, (const half_t *)x, (const half_t *)scale, y)
+    switch (nw) {
+        case 2: QTIP_MV_LAUNCH(2); break;
+        case 4: QTIP_MV_LAUNCH(4); break;
+        case 16: QTIP_MV_LAUNCH(16); break;
+        default: QTIP_MV_LAUNCH(8); break;
+    }
+#undef QTIP_MV_LAUNCH
     return hipGetLastError();
 }
 
