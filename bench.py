@@ -180,7 +180,7 @@ def main():
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        rows = 512
+        rows = 2048
         tn = w.n // 16
         slab = st["inp"].codes[: (rows // 16) * tn]
         xt = st["xt"].cpu().numpy()

@@ -245,17 +245,6 @@ __device__ __forceinline__ void align_row_words(int i, uint32_t (&w)[3]) {
     }
 }
 
-template <int K, int V, int CODE>
-__device__ __forceinline__ half8_t pack8(const half2_t (&h)[8], int half) {
-    half8_t a;
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-        a[2 * e] = h[4 * half + e].x;
-        a[2 * e + 1] = h[4 * half + e].y;
-    }
-    return a;
-}
-
 template <int K, int V, int CODE, int NB, int NW>
 __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
@@ -267,6 +256,8 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
     __shared__ uint32_t s_lut[1 << HYB_Q];
     __shared__ float s_part[NW - 1][R][NB][4][64];
     if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
+    RowDecode<K, CODE> rdec;
+    rdec.init(s_lut);
     const int I0 = blockIdx.x * R;
     const int b0 = blockIdx.y * (16 * NB);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -324,11 +315,13 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
 #pragma unroll
         for (int r = 0; r < R; r++) {
             align_row_words<K>(i, w[r]);
-            half2_t hrow[8];
-            decode_row<K, V, CODE>(w[r], 0, s_lut, hrow);
+            uint32_t hrow[8];
+            rdec.run(w[r], 0, hrow);
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                const half8_t a = pack8<K, V, CODE>(hrow, h);
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const half8_t a = __builtin_bit_cast(
+                    half8_t, u32x4{hrow[4 * h], hrow[4 * h + 1], hrow[4 * h + 2], hrow[4 * h + 3]});
 #pragma unroll
                 for (int nb = 0; nb < NB; nb++)
                     acc[r][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xb[nb][h], acc[r][nb], 0, 0, 0);

@@ -149,6 +149,85 @@ __device__ __forceinline__ void row_states(const uint32_t (&w)[NW], int rr, uint
     }
 }
 
+// Two packed weight pairs from four 3INST words: p = (sum(y0), sum(y1)), q = (sum(y2),
+// sum(y3)), each sum one binary16 add of the two halves of a word.  Interleaved like
+// add_halves_dot2x2 for the same hazard.
+__device__ __forceinline__ void add_halves_pack2x2(uint32_t y0, uint32_t y1, uint32_t y2, uint32_t y3,
+                                                   uint32_t &p, uint32_t &q) {
+    asm("v_add_f16_sdwa %0, %2, %2 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %1, %4, %4 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %0, %3, %3 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %1, %5, %5 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "s_nop 0"
+        : "=&v"(p), "=&v"(q)
+        : "v"(y0), "v"(y1), "v"(y2), "v"(y3));
+}
+
+// One tile row decoded to 8 packed fp16 pairs in column order, with the hot-loop
+// instruction sequences (same bits as the plain code functions).  Used where the
+// weights feed the matrix cores.
+template <int K, int CODE> struct RowDecode {
+    uint64_t b64;
+    uint32_t mm;
+    const uint32_t *lut;
+    __device__ __forceinline__ void init(const uint32_t *lds_lut) {
+        lut = lds_lut;
+        b64 = CODE == CODE_3INST ? INST_B : MAD_B;
+        mm = INST_MM;
+        asm volatile("" : "+v"(b64), "+v"(mm));
+    }
+    template <int NW>
+    __device__ __forceinline__ void run(const uint32_t (&w)[NW], int rr, uint32_t (&h)[8]) const {
+        if constexpr (CODE == CODE_3INST) {
+            uint32_t st[16], y[16];
+            row_states<K>(w, rr, st);
+#pragma unroll
+            for (int c = 0; c < 16; c++) y[c] = (lcg_mad64(st[c], INST_A, b64) & INST_MASK) ^ mm;
+#pragma unroll
+            for (int c = 0; c < 16; c += 4)
+                add_halves_pack2x2(y[c], y[c + 1], y[c + 2], y[c + 3], h[c / 2], h[c / 2 + 1]);
+        } else if constexpr (CODE == CODE_1MAD) {
+            uint32_t st[16];
+            row_states<K>(w, rr, st);
+#pragma unroll
+            for (int c = 0; c < 16; c += 2) {
+                float f[2];
+#pragma unroll
+                for (int e = 0; e < 2; e++) {
+                    uint32_t X = lcg_mad64(st[c + e], MAD_A, b64);
+                    uint32_t t = __builtin_amdgcn_sad_u8(X, 0u, 0x4B000000u);  // float 2^23 + s
+                    f[e] = (__builtin_bit_cast(float, t) - 8389118.0f) * MAD_INV_SCALE;
+                }
+                h[c / 2] = as_u32(half2_t{(half_t)f[0], (half_t)f[1]});
+            }
+        } else {
+            const int P0 = rr * 16 * K;
+            if constexpr (K == 2 || K == 4) {
+                constexpr int G = 8 / K;
+                uint32_t H[4];
+#pragma unroll
+                for (int base = 0, i = 0; base < 8; base += 2 * G)
+#pragma unroll
+                    for (int j = 0; j < G; j++, i++) {
+                        uint32_t R = window32(w, P0 + (base + j) * 2 * K);
+                        asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H[i]) : "v"(R));
+                    }
+#pragma unroll
+                for (int base = 0, i = 0; base < 8; base += 2 * G)
+#pragma unroll
+                    for (int j = 0; j < G; j++, i++) {
+                        // state base+j in the high half of H, state base+j+G in the low half
+                        h[base + j] = lut[(H[i] >> 22) & 0x1FFu] ^ (H[i] & 0x80000000u);
+                        h[base + j + G] = lut[(H[i] >> 6) & 0x1FFu] ^ ((H[i] & 0x8000u) << 16);
+                    }
+            } else {
+#pragma unroll
+                for (int c = 0; c < 8; c++) h[c] = as_u32(code_hyb(window16(w, P0 + c * 2 * K), lut));
+            }
+        }
+    }
+};
+
 template <int K, int CODE> struct RowDot;
 
 // 3INST, V = 1.
