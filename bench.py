@@ -33,6 +33,7 @@ WORKLOAD = "metric_3inst_k2_8192x28672"
 # profiles/matvec_3inst_k2_8192x28672_traffic.txt: FETCH_SIZE 28944.1 KiB x 1.9998 (the copy kernel reads
 # half of what it moves on this counter) + WRITE_SIZE 32.0 KiB x 1.0000.
 MEASURED_TRAFFIC_BYTES = {"metric_3inst_k2_8192x28672": 59304557}
+MEASURED_VALU_WAVE_INSTS = {"metric_3inst_k2_8192x28672": 20640000}
 
 
 def log(*a):
@@ -177,6 +178,19 @@ def main():
                 "us_per_launch_cache_resident": r["ms_hot"] * 1e3,
                 "algorithmic_bytes": alg_bytes}
 
+    # The same kernel against the vector-ALU roof: wave instructions per launch from
+    # profiles/matvec_3inst_k2_8192x28672_valu.txt (SQ_INSTS_VALU), 64 lanes each, against
+    # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second.  Some of the
+    # instructions issue in two cycles instead of four, so the fraction can pass 1.
+    valu = None
+    if w.name in MEASURED_VALU_WAVE_INSTS:
+        lane_ops = MEASURED_VALU_WAVE_INSTS[w.name] * 64
+        peak = 256 * 4 * 16 * 2.4e9
+        valu = {"bound": "alu", "kernel": "decode+matvec", "unit": "T lane-instructions/s",
+                "achieved": lane_ops / (r["ms_hot"] * 1e-3) / 1e12, "peak": peak / 1e12,
+                "frac": lane_ops / (r["ms_hot"] * 1e-3) / peak,
+                "valu_wave_instructions_per_launch": MEASURED_VALU_WAVE_INSTS[w.name]}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -244,7 +258,7 @@ def main():
         "us_per_matvec": r["ms_kernel"] * 1e3, "us_rht": r["ms_rht"] * 1e3,
         "ms_per_step_hipgraph": r["ms_step_graph"],
         "pct_of_hbm_peak": gbs(r["ms_kernel"]) / HBM_PEAK_GBS * 100,
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "roofline_alu": valu, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out), flush=True)
 

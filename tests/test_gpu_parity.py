@@ -288,3 +288,52 @@ def test_quantize_roundtrip_on_gpu(q):
         got = run_dequantize(q, w, inp).view(np.float16).astype(np.float64)
         assert abs(((got - Wsrc) ** 2).mean() - mse) < 1e-9
         assert mse / sd ** 2 < 0.09
+
+
+# ------------------------------------------------------------ randomized shapes
+
+def test_random_shapes_all_entry_points(q):
+    """Seeded random (m, n, B, codec) cases: ragged tile counts, every wave-count variant."""
+    rng = np.random.default_rng(20240611)
+    for case in range(24):
+        code_id, k, V = ALL_CODECS[int(rng.integers(0, len(ALL_CODECS)))]
+        m = 16 * int(rng.integers(1, 12))
+        n = 16 * int(rng.choice([1, 3, 7, 17, 33, 65, 129, 257, 1025]))
+        B = int(rng.choice([1, 1, 2, 5, 16, 31, 33]))
+        w = small_workload(code_id, k, V, m, n, B=B, row_scale=bool(case % 2), sub=case)
+        inp = synth.make_inputs(w, seed=w.seed + 17 * case)
+        Wref = oracle.dequantize(inp.codes, 16, k, V, code_id, m, n, inp.lut)
+        assert np.array_equal(run_dequantize(q, w, inp), Wref), (case, m, n, k)
+        ref = oracle.matmat_dense(Wref, inp.X, inp.row_scale)
+        err = rel_err(run_matmat(q, w, inp), ref)
+        assert err <= OBSERVED_TOL, (case, m, n, B, k, err)
+
+
+def test_extreme_table_values_do_not_leak_into_dead_lanes(q):
+    """HYB tables may hold infinities: lanes past the end of a ragged row must not add inf*0."""
+    w = small_workload(CODE_HYB, 2, 2, 32, 16 * 19, B=1)
+    inp = synth.make_inputs(w)
+    inp.lut[7, 0] = np.float16(np.inf)          # one entry; find rows that never use it
+    Wref = oracle.dequantize(inp.codes, 16, 2, 2, CODE_HYB, w.m, w.n, inp.lut)
+    finite_rows = np.all(np.isfinite(Wref.view(np.float16)), axis=1)
+    got = run_matmat(q, w, inp, use_matvec=True, scale=False)[0]
+    assert np.all(np.isfinite(got[finite_rows]))
+    inp.lut[7, 0] = np.float16(0.5)
+    Wref = oracle.dequantize(inp.codes, 16, 2, 2, CODE_HYB, w.m, w.n, inp.lut)
+    ref = oracle.matmat_dense(Wref, inp.X)
+    assert rel_err(run_matmat(q, w, inp, use_matvec=True, scale=False), ref) <= OBSERVED_TOL
+
+
+def test_stream_argument_is_honoured(q):
+    import torch
+    w = small_workload(CODE_3INST, 2, 1, 64, 512)
+    inp = synth.make_inputs(w)
+    s = torch.cuda.Stream()
+    y = torch.zeros(w.m, dtype=torch.float32, device="cuda")
+    codes, x = dev(inp.codes), dev(inp.X)
+    torch.cuda.synchronize()
+    q.qtip_decode_matvec(codes, 16, 2, 1, CODE_3INST, None, w.m, w.n, x, y, stream=s)
+    s.synchronize()
+    Wref = oracle.dequantize(inp.codes, 16, 2, 1, CODE_3INST, w.m, w.n)
+    ref = oracle.matmat_dense(Wref, inp.X)[0]
+    assert rel_err(y.cpu().numpy().astype(np.float64), ref) <= OBSERVED_TOL
