@@ -142,11 +142,7 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
     __shared__ uint32_t s_lut[CODE == CODE_HYB ? HYB_LDS_WORDS : 1];
     __shared__ float s_part[NW][16];
     if constexpr (CODE == CODE_HYB) {
-        for (int i = threadIdx.x; i < (1 << HYB_Q); i += NW * 64) {
-            const uint32_t v = lut[i];
-            s_lut[i] = v;
-            s_lut[(1 << HYB_Q) + i] = (v >> 16) | (v << 16);
-        }
+        stage_signed_lut(lut, s_lut, NW * 64);
         __syncthreads();
     }
     RowDot<K, CODE> rd;
@@ -253,9 +249,12 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
                                                          float *__restrict__ Y) {
     constexpr int R = 2;
     constexpr int NWORDS = 8 * K;
-    __shared__ uint32_t s_lut[1 << HYB_Q];
+    __shared__ uint32_t s_lut[CODE == CODE_HYB ? HYB_LDS_WORDS : 1];
     __shared__ float s_part[NW - 1][R][NB][4][64];
-    if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
+    if constexpr (CODE == CODE_HYB) {
+        stage_signed_lut(lut, s_lut, NW * 64);
+        __syncthreads();
+    }
     RowDecode<K, CODE> rdec;
     rdec.init(s_lut);
     const int I0 = blockIdx.x * R;

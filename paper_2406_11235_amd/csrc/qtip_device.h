@@ -163,6 +163,20 @@ __device__ __forceinline__ void add_halves_pack2x2(uint32_t y0, uint32_t y1, uin
         : "v"(y0), "v"(y1), "v"(y2), "v"(y3));
 }
 
+// The 1024 signed HYB vectors in LDS (see RowDot<K, CODE_HYB>): staging and lookup.
+constexpr int HYB_LDS_WORDS = 2 << HYB_Q;
+__device__ __forceinline__ void stage_signed_lut(const uint32_t *__restrict__ lut, uint32_t *s_lut,
+                                                 int nthreads) {
+    for (int i = threadIdx.x; i < (1 << HYB_Q); i += nthreads) {
+        const uint32_t v = lut[i];
+        s_lut[i] = v;
+        s_lut[(1 << HYB_Q) + i] = v ^ 0x80000000u;
+    }
+}
+__device__ __forceinline__ uint32_t hyb_signed_lookup(const uint32_t *s_lut, uint32_t byte_addr) {
+    return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(s_lut) + byte_addr);
+}
+
 // One tile row decoded to 8 packed fp16 pairs in column order, with the hot-loop
 // instruction sequences (same bits as the plain code functions).  Used where the
 // weights feed the matrix cores.
@@ -201,28 +215,27 @@ template <int K, int CODE> struct RowDecode {
                 h[c / 2] = as_u32(half2_t{(half_t)f[0], (half_t)f[1]});
             }
         } else {
-            const int P0 = rr * 16 * K;
+            const int P0 = rr * 16 * K;  // lut is the 1024-entry signed table
             if constexpr (K == 2 || K == 4) {
                 constexpr int G = 8 / K;
-                uint32_t H[4];
 #pragma unroll
-                for (int base = 0, i = 0; base < 8; base += 2 * G)
+                for (int base = 0; base < 8; base += 2 * G)
 #pragma unroll
-                    for (int j = 0; j < G; j++, i++) {
-                        uint32_t R = window32(w, P0 + (base + j) * 2 * K);
-                        asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H[i]) : "v"(R));
-                    }
-#pragma unroll
-                for (int base = 0, i = 0; base < 8; base += 2 * G)
-#pragma unroll
-                    for (int j = 0; j < G; j++, i++) {
+                    for (int j = 0; j < G; j++) {
+                        const uint32_t R = window32(w, P0 + (base + j) * 2 * K);
+                        uint32_t H;
+                        asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H) : "v"(R));
                         // state base+j in the high half of H, state base+j+G in the low half
-                        h[base + j] = lut[(H[i] >> 22) & 0x1FFu] ^ (H[i] & 0x80000000u);
-                        h[base + j + G] = lut[(H[i] >> 6) & 0x1FFu] ^ ((H[i] & 0x8000u) << 16);
+                        h[base + j] = hyb_signed_lookup(lut, (H >> 20) & 0xFFCu);
+                        h[base + j + G] = hyb_signed_lookup(lut, (H >> 4) & 0xFFCu);
                     }
             } else {
 #pragma unroll
-                for (int c = 0; c < 8; c++) h[c] = as_u32(code_hyb(window16(w, P0 + c * 2 * K), lut));
+                for (int c = 0; c < 8; c++) {
+                    const uint32_t st = window16(w, P0 + c * 2 * K);
+                    const uint32_t X = st * st + st;
+                    h[c] = hyb_signed_lookup(lut, (X >> 4) & 0xFFCu);
+                }
             }
         }
     }
@@ -295,24 +308,15 @@ template <int K> struct RowDot<K, CODE_1MAD> {
     }
 };
 
-// HYB, V = 2: the LUT sits in LDS twice, once as stored (entry 0 low, entry 1
-// high) and once with the halves swapped, so that the sign bit of the hash lines
-// up with entry 1 whichever half of a packed register the hash sits in.
-constexpr int HYB_LDS_WORDS = 2 << HYB_Q;
+// HYB, V = 2.  Bit 15 of the hash negates entry 1 and bits 6..14 pick the row, so
+// bits 6..15 together index 2^(Q+1) = 1024 signed vectors (Section 3.1.2 puts it the
+// same way); the hot loop reads that 4 KiB table from LDS, built by the kernel from the
+// 512 stored rows: signed[s * 512 + idx] = row idx with entry 1 negated iff s.  One
+// shift and one mask turn a hash into a byte address, and no sign fix-up is left.
 template <int K> struct RowDot<K, CODE_HYB> {
-    const uint32_t *lut;  // LDS: [0, 512) stored order, [512, 1024) halves swapped
+    const uint32_t *lut;  // LDS: the 1024 signed vectors
     __device__ __forceinline__ void init(const uint32_t *lds_lut) { lut = lds_lut; }
-    // activations that meet a swapped table entry get their halves swapped too
-    __device__ __forceinline__ void prep_x(uint32_t (&x)[8]) const {
-        if constexpr (K == 2 || K == 4) {
-            constexpr int G = 8 / K;
-#pragma unroll
-            for (int base = 0; base < 8; base += 2 * G)
-#pragma unroll
-                for (int j = 0; j < G; j++)
-                    x[base + j + G] = __builtin_amdgcn_alignbit(x[base + j + G], x[base + j + G], 16);
-        }
-    }
+    __device__ __forceinline__ void prep_x(uint32_t (&)[8]) const {}
     // All RPL rows of this lane, software-pipelined by row: the hashes and the eight
     // table reads of row r+1 are issued before the reads of row r are consumed, so
     // a wave keeps the LDS and the vector ALU busy at the same time by itself.
@@ -323,21 +327,20 @@ template <int K> struct RowDot<K, CODE_HYB> {
                                              float (&acc)[RPL]) const {
         if constexpr (K == 2 || K == 4) {
             constexpr int G = 8 / K;  // states between the two halves of a window
-            uint32_t H[RPL][4], v[RPL][8];
+            uint32_t v[RPL][8];
             auto issue_row = [&](int rr) {
 #pragma unroll
-                for (int base = 0, i = 0; base < 8; base += 2 * G)
+                for (int base = 0; base < 8; base += 2 * G)
 #pragma unroll
-                    for (int j = 0; j < G; j++, i++) {
-                        uint32_t R = window32(w, rr * 16 * K + (base + j) * 2 * K);
+                    for (int j = 0; j < G; j++) {
+                        const uint32_t R = window32(w, rr * 16 * K + (base + j) * 2 * K);
                         // both hashes at once: low 16 bits of x*x + x in each half
-                        asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H[rr][i]) : "v"(R));
+                        uint32_t H;
+                        asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H) : "v"(R));
+                        // hash bits 6..15 -> byte address; state base+j sits in the high half
+                        v[rr][base + j] = hyb_signed_lookup(lut, (H >> 20) & 0xFFCu);
+                        v[rr][base + j + G] = hyb_signed_lookup(lut, (H >> 4) & 0xFFCu);
                     }
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    v[rr][2 * i] = lut[(H[rr][i] >> 22) & 0x1FFu];             // high: stored order
-                    v[rr][2 * i + 1] = lut[512 + ((H[rr][i] >> 6) & 0x1FFu)];  // low: swapped
-                }
             };
             issue_row(0);
 #pragma unroll
@@ -345,15 +348,8 @@ template <int K> struct RowDot<K, CODE_HYB> {
                 if (rr + 1 < RPL) issue_row(rr + 1);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int base = 0, i = 0; base < 8; base += 2 * G)
-#pragma unroll
-                    for (int j = 0; j < G; j++, i++) {
-                        // sign of the hash: bit 31 for the high half, bit 15 for the low half
-                        uint32_t vh = v[rr][2 * i] ^ (H[rr][i] & 0x80000000u);
-                        uint32_t vl = v[rr][2 * i + 1] ^ (H[rr][i] & 0x8000u);
-                        acc[rr] = __builtin_amdgcn_fdot2(as_half2(vh), as_half2(x[base + j]), acc[rr], false);
-                        acc[rr] = __builtin_amdgcn_fdot2(as_half2(vl), as_half2(x[base + j + G]), acc[rr], false);
-                    }
+                for (int c = 0; c < 8; c++)
+                    acc[rr] = __builtin_amdgcn_fdot2(as_half2(v[rr][c]), as_half2(x[c]), acc[rr], false);
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
@@ -361,8 +357,10 @@ template <int K> struct RowDot<K, CODE_HYB> {
             for (int rr = 0; rr < RPL; rr++)
 #pragma unroll
                 for (int c = 0; c < 8; c++) {
-                    half2_t hv = code_hyb(window16(w, rr * 16 * K + c * 2 * K), lut);
-                    acc[rr] = __builtin_amdgcn_fdot2(hv, as_half2(x[c]), acc[rr], false);
+                    const uint32_t st = window16(w, rr * 16 * K + c * 2 * K);
+                    const uint32_t X = st * st + st;
+                    acc[rr] = __builtin_amdgcn_fdot2(as_half2(hyb_signed_lookup(lut, (X >> 4) & 0xFFCu)),
+                                                     as_half2(x[c]), acc[rr], false);
                 }
         }
     }
