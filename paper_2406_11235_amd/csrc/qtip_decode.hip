@@ -149,6 +149,11 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
     rd.init(s_lut);
     const int I = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // The waves of a workgroup start together and run the same instruction sequence, so
+    // they stay in phase and ask for the same pipe at the same time.  A start offset of a
+    // few hundred cycles per wave breaks that up: measured 5 % on the long 3INST kernel,
+    // neutral on the short ones.
+    for (int i = 0; i < (wave & 7); i++) __builtin_amdgcn_s_sleep(2);
     const int g = lane / LPT, q = lane & (LPT - 1);
     const int chunk = ((tn + NW * TPI - 1) / (NW * TPI)) * TPI;
     const int J0 = wave * chunk;
