@@ -110,23 +110,6 @@ __device__ __forceinline__ uint32_t lcg_mad64(uint32_t x, uint32_t a, uint64_t b
     return (uint32_t)d;
 }
 
-// acc += (lo(y0)+hi(y0)) * lo(x) + (lo(y1)+hi(y1)) * hi(x), twice: each fp16 sum
-// is one binary16 add written into one half of a packed register, then a dot2.
-// The two pairs are interleaved so that no instruction reads a register half-
-// written by the instruction just before it (a one-cycle hazard on this ISA).
-__device__ __forceinline__ void add_halves_dot2x2(uint32_t y0, uint32_t y1, uint32_t y2, uint32_t y3,
-                                                  uint32_t xa, uint32_t xb, float &acc) {
-    uint32_t p, q;
-    asm("v_add_f16_sdwa %0, %3, %3 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
-        "v_add_f16_sdwa %1, %5, %5 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
-        "v_add_f16_sdwa %0, %4, %4 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1\n\t"
-        "v_add_f16_sdwa %1, %6, %6 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1\n\t"
-        "v_dot2c_f32_f16 %2, %0, %7\n\t"
-        "v_dot2c_f32_f16 %2, %1, %8"
-        : "=&v"(p), "=&v"(q), "+v"(acc)
-        : "v"(y0), "v"(y1), "v"(y2), "v"(y3), "v"(xa), "v"(xb));
-}
-
 // The 16 zero-extended states of tile row rr of this lane's words.
 template <int K, int NW>
 __device__ __forceinline__ void row_states(const uint32_t (&w)[NW], int rr, uint32_t (&st)[16]) {
@@ -150,8 +133,10 @@ __device__ __forceinline__ void row_states(const uint32_t (&w)[NW], int rr, uint
 }
 
 // Two packed weight pairs from four 3INST words: p = (sum(y0), sum(y1)), q = (sum(y2),
-// sum(y3)), each sum one binary16 add of the two halves of a word.  Interleaved like
-// add_halves_dot2x2 for the same hazard.
+// sum(y3)), each sum one binary16 add of the two halves of a word, written straight
+// into one half of a packed register (SDWA).  The two pairs are interleaved so that no
+// instruction reads a register half-written by the instruction just before it (a
+// one-cycle hazard on this ISA); the trailing s_nop covers the first user.
 __device__ __forceinline__ void add_halves_pack2x2(uint32_t y0, uint32_t y1, uint32_t y2, uint32_t y3,
                                                    uint32_t &p, uint32_t &q) {
     asm("v_add_f16_sdwa %0, %2, %2 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
@@ -175,6 +160,32 @@ __device__ __forceinline__ void stage_signed_lut(const uint32_t *__restrict__ lu
 }
 __device__ __forceinline__ uint32_t hyb_signed_lookup(const uint32_t *s_lut, uint32_t byte_addr) {
     return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(s_lut) + byte_addr);
+}
+
+// acc += p . xa + q . xb for the packed pairs of the previous group, then the next
+// group's four fp16 sums into the same p and q.  Order: the dot products read p and q
+// first (their halves were written at least two instructions earlier), then the four
+// SDWA adds rewrite them, interleaved as in add_halves_pack2x2.
+__device__ __forceinline__ void dot2x2_add_halves(uint32_t &p, uint32_t &q, uint32_t xa, uint32_t xb,
+                                                  float &acc, uint32_t y0, uint32_t y1, uint32_t y2,
+                                                  uint32_t y3) {
+    asm("v_dot2c_f32_f16 %2, %0, %7\n\t"
+        "v_dot2c_f32_f16 %2, %1, %8\n\t"
+        "v_add_f16_sdwa %0, %3, %3 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %1, %5, %5 dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %0, %4, %4 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1\n\t"
+        "v_add_f16_sdwa %1, %6, %6 dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:WORD_0 src1_sel:WORD_1"
+        : "+v"(p), "+v"(q), "+v"(acc)
+        : "v"(y0), "v"(y1), "v"(y2), "v"(y3), "v"(xa), "v"(xb));
+}
+// The last group's dot products, followed by the wait states the dot unit needs before
+// another kind of instruction may read or overwrite its result.
+__device__ __forceinline__ void dot2x2_tail(uint32_t p, uint32_t q, uint32_t xa, uint32_t xb, float &acc) {
+    asm("v_dot2c_f32_f16 %0, %1, %3\n\t"
+        "v_dot2c_f32_f16 %0, %2, %4\n\t"
+        "s_nop 3"
+        : "+v"(acc)
+        : "v"(p), "v"(q), "v"(xa), "v"(xb));
 }
 
 // One tile row decoded to 8 packed fp16 pairs in column order, with the hot-loop
@@ -261,9 +272,16 @@ template <int K> struct RowDot<K, CODE_3INST> {
         row_states<K>(w, rr, st);
 #pragma unroll
         for (int c = 0; c < 16; c++) y[c] = (lcg_mad64(st[c], INST_A, b64) & INST_MASK) ^ mm;
+        // Software-pipelined by groups of four weights: a group's two dot products are
+        // issued at the head of the next group's block, so that every block ends with four
+        // SDWA adds and the dot unit's results are old enough (three wait states) before any
+        // instruction outside the blocks can touch the accumulator.
+        uint32_t p, q;
+        add_halves_pack2x2(y[0], y[1], y[2], y[3], p, q);
 #pragma unroll
-        for (int c = 0; c < 16; c += 4)
-            add_halves_dot2x2(y[c], y[c + 1], y[c + 2], y[c + 3], x[c / 2], x[c / 2 + 1], acc);
+        for (int c = 4; c < 16; c += 4)
+            dot2x2_add_halves(p, q, x[c / 2 - 2], x[c / 2 - 1], acc, y[c], y[c + 1], y[c + 2], y[c + 3]);
+        dot2x2_tail(p, q, x[6], x[7], acc);
     }
     template <int NW, int RPL>
     __device__ __forceinline__ void run_tile(const uint32_t (&w)[NW], const uint32_t (&x)[8],
