@@ -12,7 +12,8 @@ import numpy as np
 CODE_1MAD, CODE_3INST, CODE_HYB = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libqtip.so")
+# QTIP_LIBRARY points at another build of the same library (e.g. to compare two builds)
+_LIB_PATH = os.environ.get("QTIP_LIBRARY") or os.path.join(_HERE, "libqtip.so")
 _lib = None
 
 EXPORTS = ["qtip_rht", "qtip_rht_f32", "qtip_decode_matvec", "qtip_decode_matmat",

@@ -23,17 +23,17 @@ def is_stale():
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force=True, extra_flags=(), verbose=False):
-    """Compile every source into paper_2406_11235_amd/libqtip.so."""
-    if not force and not is_stale():
+def build(force=True, extra_flags=(), verbose=False, out=None):
+    """Compile every source into paper_2406_11235_amd/libqtip.so (or `out`)."""
+    if out is None and not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + FLAGS + list(extra_flags) + ["-x", "hip"] + \
-          [os.path.join(CSRC, f) for f in SOURCES] + ["-o", LIB]
+          [os.path.join(CSRC, f) for f in SOURCES] + ["-o", out or LIB]
     if verbose:
         print(" ".join(cmd), file=sys.stderr)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":
