@@ -227,6 +227,12 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
 // A wave owns R = 2 neighbouring tile rows so that every B operand it loads feeds
 // two MFMAs; NB groups of 16 batch rows share every decoded weight.  The waves of
 // a workgroup split the tiles of the row band and meet in LDS.
+// The B operand puts neighbouring lanes on different batch rows, that is on different
+// cache lines, and the texture path serves such a 16-byte-per-lane load at a fraction
+// of the rate of one whose neighbouring lanes read neighbouring addresses.  With few
+// distinct batch rows that does not matter; at larger batch (STAGE) a wave loads its
+// activations line by line (8 lanes = the 128 bytes that one batch row has under the
+// four tiles of a step) and transposes them through a private piece of LDS.
 
 // The words that hold tile row i (16 K bits from bit 16 K i) and the 16 - K V bits
 // after it, brought to bit offset 0; indices wrap inside the tile (tail-biting).
@@ -251,7 +257,7 @@ __device__ __forceinline__ void align_row_words(int i, uint32_t (&w)[3]) {
     }
 }
 
-template <int K, int V, int CODE, int NB, int NW>
+template <int K, int V, int CODE, int NB, int NW, bool STAGE>
 __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
                                                          int tm, int tn, const half_t *__restrict__ X,
@@ -260,7 +266,14 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
     constexpr int R = 2;
     constexpr int NWORDS = 8 * K;
     __shared__ uint32_t s_lut[CODE == CODE_HYB ? HYB_LDS_WORDS : 1];
-    __shared__ float s_part[NW - 1][R][NB][4][64];
+    // one buffer, used twice: in the loop each wave's staging region (SR batch rows at a
+    // time, 128 bytes each, padded to 144 so that the row-wise writes and the
+    // column-wise reads both spread over the banks), after it the partial sums
+    constexpr int SR = NB >= 2 ? 32 : 16, NH = 16 * NB / SR, XST = 144;
+    constexpr int PART_FLOATS = (NW - 1) * R * NB * 256;
+    constexpr int STAGE_FLOATS = STAGE ? NW * SR * XST / 4 : 0;
+    __shared__ __attribute__((aligned(16))) float s_buf[PART_FLOATS > STAGE_FLOATS ? PART_FLOATS : STAGE_FLOATS];
+    float(*s_part)[R][NB][4][64] = reinterpret_cast<float(*)[R][NB][4][64]>(s_buf);
     if constexpr (CODE == CODE_HYB) {
         stage_signed_lut(lut, s_lut, NW * 64);
         __syncthreads();
@@ -286,7 +299,9 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
 
     // software pipeline: operands of step t+1 are loaded while step t runs
     uint32_t wn[R][3];
-    half8_t xn[NB][2];
+    half8_t xn[NB][2];  // STAGE: piece (lane % 8) of batch rows 8 q + lane / 8, q = 2 nb + h
+    const int lr = lane >> 3, ch = lane & 7;
+    char *const stage = reinterpret_cast<char *>(s_buf) + wave * (SR * XST);
     auto issue = [&](int Jb) {
         const int J = min(Jb + s, Jend - 1);  // slots past the end re-read the last tile
 #pragma unroll
@@ -294,12 +309,22 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
             const int I = row_ok[r] ? I0 + r : I0;
             load_row_words<K>(codes + ((size_t)I * tn + J) * NWORDS, i, wn[r]);
         }
+        if constexpr (STAGE) {
+            const int Jx = min(Jb + (ch >> 1), Jend - 1);
 #pragma unroll
-        for (int nb = 0; nb < NB; nb++) {
-            const int b = b0 + 16 * nb + i;
-            const half_t *xp = X + (size_t)min(b, B - 1) * n + 16 * J;
-            xn[nb][0] = *reinterpret_cast<const half8_t *>(xp);
-            xn[nb][1] = *reinterpret_cast<const half8_t *>(xp + 8);
+            for (int q = 0; q < 2 * NB; q++) {
+                const int b = b0 + 8 * q + lr;
+                xn[q >> 1][q & 1] = *reinterpret_cast<const half8_t *>(
+                    X + (size_t)min(b, B - 1) * n + 16 * Jx + 8 * (ch & 1));
+            }
+        } else {
+#pragma unroll
+            for (int nb = 0; nb < NB; nb++) {
+                const int b = b0 + 16 * nb + i;
+                const half_t *xp = X + (size_t)min(b, B - 1) * n + 16 * J;
+                xn[nb][0] = *reinterpret_cast<const half8_t *>(xp);
+                xn[nb][1] = *reinterpret_cast<const half8_t *>(xp + 8);
+            }
         }
     };
     if (J0 < Jend) issue(J0);
@@ -311,12 +336,37 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
 #pragma unroll
             for (int t = 0; t < 3; t++) w[r][t] = wn[r][t];
         const bool live = Jb + s < Jend;
+        if constexpr (STAGE) {
+            // The lanes of the wave exchange data through LDS without a workgroup barrier:
+            // the LDS operations of one wave complete in order, and the fences keep the
+            // compiler from moving them across each other.
+#pragma unroll
+            for (int hf = 0; hf < NH; hf++) {
+#pragma unroll
+                for (int qq = 0; qq < SR / 8; qq++) {
+                    const int q = hf * (SR / 8) + qq;
+                    *reinterpret_cast<half8_t *>(stage + (8 * qq + lr) * XST + 16 * ch) = xn[q >> 1][q & 1];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int nbb = 0; nbb < SR / 16; nbb++)
+#pragma unroll
+                    for (int h = 0; h < 2; h++)
+                        xb[hf * (SR / 16) + nbb][h] = *reinterpret_cast<const half8_t *>(
+                            stage + (16 * nbb + i) * XST + 16 * (2 * s + h));
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) {
             const bool bok = live && (b0 + 16 * nb + i < B);
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                xb[nb][h] = xn[nb][h];
+                if constexpr (!STAGE) xb[nb][h] = xn[nb][h];
                 if (!bok) xb[nb][h] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};  // dead slot / batch row
             }
         }
@@ -337,6 +387,7 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
             }
         }
     }
+    if constexpr (STAGE) __syncthreads();  // the staging regions become the partial sums
     if (wave > 0) {
 #pragma unroll
         for (int r = 0; r < R; r++)
@@ -430,16 +481,19 @@ static hipError_t launch_matmat_t(const uint32_t *codes, const uint32_t *lut, in
     const int groups = (B + 15) / 16;
     const int tm = m / 16, tn = n / 16;
     const dim3 block(NW * 64);
-    if (groups == 1) {
-        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW>), dim3((tm + 1) / 2, 1), block, 0, st,
-                           codes, lut, tm, tn, (const half_t *)X, B, (const half_t *)scale, Y);
+    const half_t *Xh = (const half_t *)X, *sc = (const half_t *)scale;
+    if (groups == 1 && B <= 8) {  // few distinct batch rows: load the B operand directly
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW, false>), dim3((tm + 1) / 2, 1), block, 0,
+                           st, codes, lut, tm, tn, Xh, B, sc, Y);
+    } else if (groups == 1) {
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW, true>), dim3((tm + 1) / 2, 1), block, 0,
+                           st, codes, lut, tm, tn, Xh, B, sc, Y);
     } else if (groups == 2) {
-        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 2, NW>), dim3((tm + 1) / 2, 1), block, 0, st,
-                           codes, lut, tm, tn, (const half_t *)X, B, (const half_t *)scale, Y);
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 2, NW, true>), dim3((tm + 1) / 2, 1), block, 0,
+                           st, codes, lut, tm, tn, Xh, B, sc, Y);
     } else {
-        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 4, NW>), dim3((tm + 1) / 2, (groups + 3) / 4),
-                           block, 0, st, codes, lut, tm, tn, (const half_t *)X, B,
-                           (const half_t *)scale, Y);
+        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 4, NW, true>), dim3((tm + 1) / 2, (groups + 3) / 4),
+                           block, 0, st, codes, lut, tm, tn, Xh, B, sc, Y);
     }
     return hipGetLastError();
 }

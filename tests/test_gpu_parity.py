@@ -144,6 +144,22 @@ def test_matmat_small_with_row_scale(q, code_id, k, V, B):
     assert rel_err(run_matmat(q, w, inp, scale=False), ref_ns) <= OBSERVED_TOL
 
 
+@pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
+@pytest.mark.parametrize("m,n,B", [(304, 1104, 16), (304, 4112, 33), (1040, 1104, 64), (272, 8208, 80)])
+def test_matmat_large_batch_staged_activations(q, code_id, k, V, m, n, B):
+    """Batches above 8 take the path that transposes activations through LDS: odd numbers of
+    tile rows, row bands whose last step is partial (n/16 not a multiple of 4 per wave),
+    ragged batch tails, and Y pre-filled with NaN by run_matmat."""
+    w = small_workload(code_id, k, V, m, n, B=B, row_scale=True, sub=B + 1)
+    inp = synth.make_inputs(w)
+    Wref = oracle.dequantize(inp.codes, 16, k, V, code_id, m, n, inp.lut)
+    ref = oracle.matmat_dense(Wref, inp.X, inp.row_scale)
+    got = run_matmat(q, w, inp)
+    err = rel_err(got, ref)
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    assert np.array_equal(run_matmat(q, w, inp), got)  # fixed summation order
+
+
 FULL = ["cfg1_3inst_k2_1024x1024", "cfg2_3inst_k2_4096x4096", "cfg3_1mad_k2_14336x4096",
         "cfg3_1mad_k3_14336x4096", "cfg3_1mad_k4_14336x4096", "cfg3_1mad_k2_4096x14336",
         "cfg3_1mad_k3_4096x14336", "cfg3_1mad_k4_4096x14336", "cfg4_hyb_k2_8192x28672",
