@@ -81,6 +81,10 @@ def lib():
         L.orc_states_to_stream.argtypes = [vp, i32, i32, i32, vp]
         L.orc_tailbiting_quantize.restype = dbl
         L.orc_tailbiting_quantize.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.orc_viterbi_f32.restype = c.c_float
+        L.orc_viterbi_f32.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp]
+        L.orc_tailbiting_quantize_f32.restype = c.c_float
+        L.orc_tailbiting_quantize_f32.argtypes = [vp, i32, i32, i32, i32, vp, vp]
         L.orc_stream_distortion.restype = dbl
         L.orc_stream_distortion.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         L.orc_exhaustive_tailbiting.restype = dbl
@@ -268,6 +272,30 @@ def tailbiting_quantize(S, L, k, V, C):
     words = np.zeros((k * T + 31) // 32, dtype=np.uint32)
     d = lib().orc_tailbiting_quantize(_p(S), T, L, k, V, _p(C), _p(words))
     return float(d), words
+
+
+def _f32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+
+
+def viterbi_f32(S, L, k, V, C, first_top=-1, last_low=-1):
+    """Viterbi with the value function in binary32 (see orc_viterbi_f32)."""
+    S = _f32(S)
+    T = S.size
+    C = _f32(C).reshape(1 << L, V)
+    st = np.zeros(T // V, dtype=np.uint32)
+    d = lib().orc_viterbi_f32(_p(S), T, L, k, V, _p(C), first_top, last_low, _p(st))
+    return np.float32(d), st
+
+
+def tailbiting_quantize_f32(S, L, k, V, C):
+    """Algorithm 4 with binary32 Viterbi calls; returns (final value as float32, words)."""
+    S = _f32(S)
+    T = S.size
+    C = _f32(C).reshape(1 << L, V)
+    words = np.zeros((k * T + 31) // 32, dtype=np.uint32)
+    d = lib().orc_tailbiting_quantize_f32(_p(S), T, L, k, V, _p(C), _p(words))
+    return np.float32(d), words
 
 
 def stream_distortion(words, S, L, k, V, C):

@@ -21,7 +21,8 @@
  *     (Section 2.1);
  *   - the Viterbi algorithm on the bitshift trellis (Section 2.3), the
  *     tail-biting approximation (Algorithm 4) and exhaustive searches for
- *     tiny problems.
+ *     tiny problems; the same two in binary32, operation by operation, for
+ *     checking a single-precision quantizer decision by decision.
  *
  * Storage convention (the paper fixes only the logical bit order, through
  * Figure 1: the first stored bit is the most significant bit of the first
@@ -472,6 +473,107 @@ double orc_tailbiting_quantize(const double *S, int T, int L, int k, int V, cons
     /* group half/V - 1 (0-based) is the original's last, group half/V its first */
     uint32_t O = st[half / V - 1] & ((1u << ov) - 1u);
     double d = orc_viterbi(S, T, L, k, V, C, (int)O, (int)O, st);
+    orc_states_to_stream(st, G, L, kV, words);
+    free(Sr);
+    free(st);
+    return d;
+}
+
+/*
+ * The same Viterbi recursion carried in binary32, for checking a quantizer
+ * that keeps its value function in single precision: the paper does not fix
+ * the precision of the search, and a different precision can decide
+ * near-ties differently, so both sides take the decisions in this one.
+ * Every operation is a single correctly rounded binary32 operation, in this
+ * order (no fused multiply-add; the file is built with contraction off):
+ *   e_j = C[y][j] - S[V t + j];  d = e_0*e_0  (V = 1)  or  (e_0*e_0) + (e_1*e_1)  (V = 2);
+ *   value(y) = min over predecessors + d.
+ * Minima and ties are as in orc_viterbi.  V <= 2.
+ */
+float orc_viterbi_f32(const float *S, int T, int L, int k, int V, const float *C,
+                      int first_top, int last_low, uint32_t *states_out) {
+    int kV = k * V;
+    int G = T / V;
+    uint32_t NS = 1u << L;
+    uint32_t nin = 1u << kV;
+    int ov = L - kV;
+    uint32_t ovmask = (1u << ov) - 1u;
+    float *val = (float *)malloc(sizeof(float) * NS);
+    float *nxt = (float *)malloc(sizeof(float) * NS);
+    uint32_t *back = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)NS * G);
+    if (!val || !nxt || !back || V > 2) {
+        free(val);
+        free(nxt);
+        free(back);
+        return -1.0f;
+    }
+    for (int t = 0; t < G; t++) {
+        for (uint32_t y = 0; y < NS; y++) {
+            float e0 = C[(size_t)y * V] - S[V * t];
+            float d = e0 * e0;
+            if (V == 2) {
+                float e1 = C[(size_t)y * V + 1] - S[V * t + 1];
+                float d1 = e1 * e1;
+                d = d + d1;
+            }
+            if (t == 0) {
+                if (first_top >= 0 && (y >> kV) != (uint32_t)first_top) d = INFINITY;
+                nxt[y] = d;
+                continue;
+            }
+            float best = INFINITY;
+            uint32_t arg = 0;
+            for (uint32_t p = 0; p < nin; p++) {
+                uint32_t x = (p << ov) | (y >> kV);
+                if (val[x] < best) {
+                    best = val[x];
+                    arg = x;
+                }
+            }
+            nxt[y] = best + d;
+            back[(size_t)t * NS + y] = arg;
+        }
+        float *tmp = val;
+        val = nxt;
+        nxt = tmp;
+    }
+    float best = INFINITY;
+    uint32_t arg = 0;
+    for (uint32_t y = 0; y < NS; y++) {
+        if (last_low >= 0 && (y & ovmask) != (uint32_t)last_low) continue;
+        if (val[y] < best) {
+            best = val[y];
+            arg = y;
+        }
+    }
+    for (int t = G - 1; t >= 0; t--) {
+        states_out[t] = arg;
+        if (t > 0) arg = back[(size_t)t * NS + arg];
+    }
+    free(val);
+    free(nxt);
+    free(back);
+    return best;
+}
+
+/* Algorithm 4 with the binary32 recursion above in both of its Viterbi calls. */
+float orc_tailbiting_quantize_f32(const float *S, int T, int L, int k, int V, const float *C,
+                                  uint32_t *words) {
+    int kV = k * V;
+    int G = T / V;
+    int ov = L - kV;
+    int half = T / 2;
+    float *Sr = (float *)malloc(sizeof(float) * (size_t)T);
+    uint32_t *st = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)G);
+    if (!Sr || !st) {
+        free(Sr);
+        free(st);
+        return -1.0f;
+    }
+    for (int i = 0; i < T; i++) Sr[(i + half) % T] = S[i];
+    orc_viterbi_f32(Sr, T, L, k, V, C, -1, -1, st);
+    uint32_t O = st[half / V - 1] & ((1u << ov) - 1u);
+    float d = orc_viterbi_f32(S, T, L, k, V, C, (int)O, (int)O, st);
     orc_states_to_stream(st, G, L, kV, words);
     free(Sr);
     free(st);

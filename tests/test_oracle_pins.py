@@ -409,3 +409,91 @@ def test_paper_mse_tables_loose(golden):
                        for _ in range(10)]) / 256 / sd ** 2
         assert abs(mse / t1[name] - 1) < 0.08, (name, mse)
         assert mse > t1["DR"]                       # above the distortion-rate bound
+
+
+# ------------------------------------------------- the binary32 Viterbi recursion
+
+def _walk_cost64(states, S, V, C):
+    G = len(states)
+    return float(sum(((C[states[t]] - S[V * t:V * t + V]) ** 2).sum() for t in range(G)))
+
+
+@pytest.mark.parametrize("L,k,V,T", [(6, 2, 1, 20), (8, 2, 2, 24), (7, 3, 1, 12), (8, 4, 1, 10)])
+def test_viterbi_f32_equals_f64_when_arithmetic_is_exact(L, k, V, T):
+    """Values on a coarse dyadic grid: every binary32 operation is exact, so decisions,
+    ties included (the grid makes many), must agree with the binary64 recursion, with
+    and without the constraints of Algorithm 4's second call."""
+    rng = np.random.default_rng(1000 + L + k)
+    C = rng.integers(-8, 9, (1 << L, V)) / 4.0
+    S = rng.integers(-8, 9, T) / 4.0
+    ov = L - k * V
+    for ft, ll in ((-1, -1), (3, 3), (5, -1), (-1, (1 << ov) - 1)):
+        d64, s64 = oracle.viterbi(S, L, k, V, C, ft, ll)
+        d32, s32 = oracle.viterbi_f32(S, L, k, V, C, ft, ll)
+        assert float(d32) == d64
+        assert np.array_equal(s32, s64)
+        if ft >= 0:
+            assert (s32[0] >> (k * V)) == ft
+        if ll >= 0:
+            assert (s32[-1] & ((1 << ov) - 1)) == ll
+    d64, w64 = oracle.tailbiting_quantize(S, L, k, V, C)
+    d32, w32 = oracle.tailbiting_quantize_f32(S, L, k, V, C)
+    assert float(d32) == d64 and np.array_equal(w32, w64)
+
+
+@pytest.mark.parametrize("L,k,V,T", [(4, 1, 1, 16), (6, 2, 1, 10), (6, 2, 2, 10), (8, 4, 1, 5)])
+def test_viterbi_f32_near_exhaustive_optimum(L, k, V, T):
+    rng = np.random.default_rng(50 + L + T)
+    for _ in range(4):
+        C = rng.standard_normal((1 << L, V)).astype(np.float16).astype(np.float64)
+        S = rng.standard_normal(T).astype(np.float32).astype(np.float64)
+        opt = oracle.exhaustive_walk(S, L, k, V, C)
+        d32, st = oracle.viterbi_f32(S, L, k, V, C)
+        # a valid walk on the trellis, whose true cost is the optimum up to binary32 rounding
+        for a, b in zip(st[:-1], st[1:]):
+            assert (int(b) >> (k * V)) == (int(a) & ((1 << (L - k * V)) - 1))
+        true = _walk_cost64(st, S, V, C)
+        assert opt - 1e-12 <= true <= opt * (1 + 1e-5) + 1e-7
+        assert abs(float(d32) - true) <= 1e-5 * true + 1e-7
+
+
+def test_viterbi_f32_operation_order_single_step():
+    """One trellis step (T = V): the value is min_y fl(fl(e0*e0) + fl(e1*e1)), every
+    operation rounded to binary32 on its own, which numpy's float32 scalars reproduce;
+    a fused multiply-add or binary64 intermediates give other bits on this sample."""
+    rng = np.random.default_rng(9)
+    L = 10
+    C = rng.standard_normal((1 << L, 2)).astype(np.float16).astype(np.float32)
+    hits = 0
+    for _ in range(50):
+        S = rng.standard_normal(2).astype(np.float32)
+        e = C - S[None, :]
+        sq = e * e                                     # float32 products
+        d = sq[:, 0] + sq[:, 1]
+        want, arg = d.min(), int(d.argmin())
+        got, st = oracle.viterbi_f32(S, L, 2, 2, C)
+        assert got == want and st[0] == arg
+        exact = ((C.astype(np.float64) - S.astype(np.float64)[None, :]) ** 2).sum(1)[arg]
+        hits += int(np.float32(exact) != want)
+    assert hits > 0          # the sample does distinguish rounding orders
+    C1 = C[:, :1].copy()
+    S1 = rng.standard_normal(1).astype(np.float32)
+    e = C1[:, 0] - S1[0]
+    got, st = oracle.viterbi_f32(S1, L, 2, 1, C1)
+    assert got == (e * e).min() and st[0] == int((e * e).argmin())
+
+
+def test_tailbiting_f32_stream_is_cyclic_and_close_to_f64():
+    rng = np.random.default_rng(31)
+    L, k, V, T = 10, 2, 1, 64
+    C = rng.standard_normal((1 << L, V)).astype(np.float16).astype(np.float64)
+    same = 0
+    for _ in range(6):
+        S = rng.standard_normal(T).astype(np.float32).astype(np.float64)
+        d32, w32 = oracle.tailbiting_quantize_f32(S, L, k, V, C)
+        true = oracle.stream_distortion(w32, S, L, k, V, C)   # cyclic decode of the stream
+        assert abs(float(d32) - true) <= 1e-5 * true
+        d64, w64 = oracle.tailbiting_quantize(S, L, k, V, C)
+        same += int(np.array_equal(w32, w64))
+        assert true <= d64 * 1.05                     # a near-tie may pick another overlap
+    assert same >= 4
