@@ -45,6 +45,7 @@
 #ifndef QTIP_H
 #define QTIP_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -133,6 +134,37 @@ int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code
  */
 int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id,
                   const void *lut_f16, uint32_t *codes_out, double *mse_out);
+
+/*
+ * GPU quantizer: the same problem as qtip_quantize -- every 16x16 tile of W
+ * quantized as one sequence by the Viterbi algorithm on the bitshift trellis
+ * (Section 2.3), made tail-biting by Algorithm 4, under squared error against the
+ * code's values (Algorithms 1-3) -- run on the device, one workgroup per tile with
+ * the 2^16-entry value function held in registers.
+ *   W:          device, m x n row-major fp32.
+ *   lut_f16:    device HYB table (NULL otherwise).
+ *   codes_out:  device, (m/16)*(n/16)*8k words, the format above.
+ *   tile_err:   device, (m/16)*(n/16) floats, or NULL: the final value of the
+ *               search for each tile = its squared reconstruction error, as
+ *               accumulated in binary32.
+ *   workspace:  device, 256-byte aligned, workspace_bytes long; holds the
+ *               back-pointers of the tiles in flight.  Any size from
+ *               qtip_quantize_gpu_workspace(k, V, 1) up works; tiles are processed
+ *               in batches of as many as fit, so give it
+ *               qtip_quantize_gpu_workspace(k, V, t) for t of a few thousand (about
+ *               1 MiB per tile at V = 1, 0.5 MiB or less at V = 2) to keep the
+ *               device full.  Contents are scratch.
+ * The search runs in binary32 with one rounding per operation (error e = c - s,
+ * squared errors summed left to right, value = minimum over predecessors + error),
+ * lowest predecessor and lowest final state on ties; the paper does not fix a
+ * precision.  Streams therefore equal a binary32 CPU search bit for bit, and may
+ * differ from a binary64 search where two walks tie to within rounding.
+ * Enqueues on `stream` and returns without synchronizing.
+ */
+size_t qtip_quantize_gpu_workspace(int k, int V, long tiles);
+int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int code_id,
+                      const void *lut_f16, uint32_t *codes_out, float *tile_err, void *workspace,
+                      size_t workspace_bytes, void *stream);
 
 /* Message for the last error on this thread ("" if none). Never NULL. */
 const char *qtip_last_error(void);

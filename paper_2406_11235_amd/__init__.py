@@ -5,9 +5,11 @@ package only marshals arguments.  torch is used for device memory and streams.
 """
 from .binding import (CODE_1MAD, CODE_3INST, CODE_HYB, QtipError, lib, library_path,
                       qtip_decode_matmat, qtip_decode_matvec, qtip_decode_states,
-                      qtip_dequantize, qtip_last_error, qtip_quantize, qtip_rht, qtip_rht_f32,
+                      qtip_dequantize, qtip_last_error, qtip_quantize, qtip_quantize_gpu,
+                      qtip_quantize_gpu_workspace, qtip_rht, qtip_rht_f32,
                       qtip_version)
 
 __all__ = ["CODE_1MAD", "CODE_3INST", "CODE_HYB", "QtipError", "lib", "library_path",
            "qtip_decode_matmat", "qtip_decode_matvec", "qtip_decode_states", "qtip_dequantize",
-           "qtip_last_error", "qtip_quantize", "qtip_rht", "qtip_rht_f32", "qtip_version"]
+           "qtip_last_error", "qtip_quantize", "qtip_quantize_gpu", "qtip_quantize_gpu_workspace",
+           "qtip_rht", "qtip_rht_f32", "qtip_version"]

@@ -17,8 +17,8 @@ _LIB_PATH = os.environ.get("QTIP_LIBRARY") or os.path.join(_HERE, "libqtip.so")
 _lib = None
 
 EXPORTS = ["qtip_rht", "qtip_rht_f32", "qtip_decode_matvec", "qtip_decode_matmat",
-           "qtip_dequantize", "qtip_decode_states", "qtip_quantize", "qtip_last_error",
-           "qtip_version"]
+           "qtip_dequantize", "qtip_decode_states", "qtip_quantize",
+           "qtip_quantize_gpu_workspace", "qtip_quantize_gpu", "qtip_last_error", "qtip_version"]
 
 
 class QtipError(RuntimeError):
@@ -63,6 +63,11 @@ def lib():
         L.qtip_decode_states.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         L.qtip_quantize.restype = i32
         L.qtip_quantize.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+        L.qtip_quantize_gpu_workspace.restype = c.c_size_t
+        L.qtip_quantize_gpu_workspace.argtypes = [i32, i32, c.c_long]
+        L.qtip_quantize_gpu.restype = i32
+        L.qtip_quantize_gpu.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp,
+                                        c.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -144,3 +149,14 @@ def qtip_quantize(W, m, n, L, k, V, code_id, lut=None):
     _check(lib().qtip_quantize(_ptr(W), m, n, L, k, V, code_id, _ptr(lut), _ptr(codes),
                                ctypes.addressof(mse)))
     return codes, float(mse.value)
+
+
+def qtip_quantize_gpu_workspace(k, V, tiles):
+    return int(lib().qtip_quantize_gpu_workspace(k, V, tiles))
+
+
+def qtip_quantize_gpu(W, m, n, L, k, V, code_id, lut, codes_out, tile_err, workspace,
+                      workspace_bytes, stream=None):
+    return _check(lib().qtip_quantize_gpu(_ptr(W), m, n, L, k, V, code_id, _ptr(lut),
+                                          _ptr(codes_out), _ptr(tile_err), _ptr(workspace),
+                                          workspace_bytes, _stream(stream)))

@@ -165,4 +165,34 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
     return QTIP_OK;
 }
 
+size_t qtip_quantize_gpu_workspace(int k, int V, long tiles) {
+    if (k < 2 || k > 4 || (V != 1 && V != 2) || tiles <= 0) return 0;
+    return qtip::quantize_gpu_workspace(k, V, tiles);
+}
+
+int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int code_id,
+                      const void *lut_f16, uint32_t *codes_out, float *tile_err, void *workspace,
+                      size_t workspace_bytes, void *stream) {
+    const char *fn = "qtip_quantize_gpu";
+    if (!W || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
+    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
+    if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
+    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
+    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (m <= 0 || n <= 0 || m % 16 || n % 16)
+        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    if (((uintptr_t)W | (uintptr_t)codes_out | (uintptr_t)tile_err) % 4 || (uintptr_t)workspace % 256)
+        return fail(QTIP_EINVAL, "%s: W, codes_out, tile_err need 4-byte, workspace 256-byte alignment", fn);
+    if (workspace_bytes < qtip::quantize_gpu_workspace(k, V, 1))
+        return fail(QTIP_EINVAL, "%s: workspace of %zu bytes cannot hold one tile (%zu needed)", fn,
+                    workspace_bytes, qtip::quantize_gpu_workspace(k, V, 1));
+    hipError_t e = qtip::launch_quantize_gpu(k, code_id, W, m, n, (const uint32_t *)lut_f16, codes_out,
+                                             tile_err, workspace, workspace_bytes, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
 }  // extern "C"

@@ -1,0 +1,407 @@
+// GPU quantizer: the Viterbi algorithm on the (16, k, V) bitshift trellis (Section 2.3 of
+// arXiv 2406.11235: value function and update rule; Section 3.1: edge rule), made
+// tail-biting by Algorithm 4, one 16x16 tile = one length-256 sequence (Section 4), for
+// the computed codes of Algorithms 1-3.
+//
+// Layout on the chip.  One workgroup of NT = 1024 threads owns one sequence and keeps the
+// whole value function, 2^16 binary32 numbers, in registers: thread `tid` holds the 64
+// states y = NT r + tid (half of the 128 registers a thread has at four waves per SIMD;
+// the code values take most of the other half).  The bitshift structure makes that layout communication-free
+// for the minimum: the 2^kV predecessors of y all end in the top 16-kV bits of y, so
+// states with a common "prefix" hi = y >> kV share one minimum, and the predecessors
+// p 2^(16-kV) + hi of a prefix have the same low 10 bits, i.e. live in one thread
+// (kV <= 6; for kV = 8 they are spread over four threads, which meet in LDS).  A step is
+//   phase 1: every thread takes the minimum and arg-minimum over the predecessors of
+//            its prefixes, publishes the minima in LDS (2^(16-kV) floats, 64 KiB at
+//            kV = 2) and stores the arg-minima, kV bits each, packed into one or two
+//            words per thread and step, to the back-pointer workspace in HBM;
+//   phase 2: every thread reads the minimum of each of its states' prefixes back from
+//            LDS and adds the squared error of the state's code value.
+// Code values never change, so they sit in registers as packed fp16 (V = 1); for the
+// HYB code a state only selects one of 1024 signed table rows, so each step first
+// builds the 1024 squared errors in LDS and states carry a 10-bit row number.
+// A second, tiny kernel walks the back-pointers (one thread per sequence: the walk is a
+// chain of dependent loads, so it is run over a whole batch of sequences at once).
+// Algorithm 4 is forward / walk-to-the-middle / constrained forward / full walk.
+//
+// Arithmetic (fixed, so that a CPU reference can repeat every decision): binary32,
+// one rounding per operation, no fused multiply-add:
+//   e_j = C[y][j] - s[V t + j];  d = e_0 e_0  or  (e_0 e_0) + (e_1 e_1);  value = min + d.
+// Minima take the lowest predecessor on ties, the final state the lowest state.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qtip_device.h"
+#include "qtip_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace qtip {
+namespace {
+
+constexpr int VT_T = 256;           // sequence length (one 16x16 tile)
+#ifndef QTIP_VITERBI_THREADS
+#define QTIP_VITERBI_THREADS 1024
+#endif
+constexpr int VT_NT = QTIP_VITERBI_THREADS;  // threads per sequence
+constexpr int VT_REGS = 65536 / VT_NT;        // states per thread
+
+template <int KV>
+struct VitGeo {
+    static constexpr int OV = 16 - KV;              // bits two consecutive states share
+    static constexpr int NP = 1 << OV;              // prefixes = minima per step
+    static constexpr int NC = 1 << KV;              // predecessors per prefix
+    static constexpr bool LOCAL = NP >= VT_NT;      // predecessors of a prefix in one thread
+    static constexpr int NB1 = LOCAL ? NP / VT_NT : 1;  // prefixes per thread
+    // back-pointers: kV bits per prefix, FPW whole fields per word, PWT words per thread
+    static constexpr int FPW = 32 / KV;
+    static constexpr int PWT = (NB1 + FPW - 1) / FPW;
+    static constexpr int PW = LOCAL ? VT_NT * PWT : NP;  // back-pointer words per step
+};
+
+__host__ __device__ constexpr int vit_max(int a, int b) { return a > b ? a : b; }
+
+// rotate = 1: the sequence rotated by T/2 (Algorithm 4's first call).  overlap != null:
+// the first state's top 16-kV bits and the last state's low 16-kV bits are forced to
+// overlap[slot] (its second call).  Sequence `slot` of the batch is tile tile0 + slot.
+template <int KV, int V, int CODE>
+__global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
+    const float *__restrict__ W, int n, int tn, long tile0, const uint32_t *__restrict__ lut, int rotate,
+    const uint32_t *__restrict__ overlap, uint32_t *__restrict__ ptrs, uint32_t *__restrict__ final_state,
+    float *__restrict__ final_value) {
+    using Geo = VitGeo<KV>;
+    constexpr int OV = Geo::OV, NP = Geo::NP, NC = Geo::NC, NB1 = Geo::NB1, PW = Geo::PW;
+    constexpr int G = VT_T / V;
+    constexpr bool HYB = CODE == CODE_HYB;
+    static_assert(HYB == (V == 2), "V = 2 is the HYB code");
+    // LDS: minima (or, for kV = 8, per-thread partial minima, their predecessors and the
+    // 256 minima), reused for the final reduction; then the HYB error table
+    constexpr int BEST_FLOATS = Geo::LOCAL ? vit_max(NP, 2 * VT_NT) : 2 * VT_NT + NP;
+    __shared__ float s_mem[BEST_FLOATS + VT_T + (HYB ? 1024 : 0)];
+    float *const s_best = s_mem;
+    float *const s_seq = s_mem + BEST_FLOATS;      // the sequence
+    float *const s_D = s_mem + BEST_FLOATS + VT_T;  // HYB only
+
+    const int tid = threadIdx.x;
+    const int slot = blockIdx.x;
+    const long tile = tile0 + slot;
+    const int I = (int)(tile / tn), J = (int)(tile % tn);
+
+    static_assert(VT_NT >= VT_T, "one thread per sequence element");
+    if (tid < VT_T) {
+        const int s = rotate ? ((tid + VT_T / 2) & (VT_T - 1)) : tid;
+        s_seq[tid] = W[(size_t)(16 * I + (s >> 4)) * n + 16 * J + (s & 15)];
+    }
+    __syncthreads();
+    auto seq = [&](int u) -> float { return s_seq[u]; };
+
+    // code values of this thread's states
+    half2_t cpk[HYB ? 1 : VT_REGS / 2];
+    uint32_t ipk[HYB ? VT_REGS / 2 : 1];
+#pragma unroll
+    for (int r = 0; r < VT_REGS; r++) {
+        const uint32_t y = (uint32_t)(r * VT_NT + tid);
+        if constexpr (HYB) {
+            const uint32_t X = y * y + y;
+            const uint32_t row = (X >> (15 - HYB_Q)) & 1023u;  // table index and sign bit
+            if (r & 1)
+                ipk[r >> 1] |= row << 16;
+            else
+                ipk[r >> 1] = row;
+        } else {
+            cpk[r >> 1][r & 1] = CODE == CODE_3INST ? code_3inst(y) : code_1mad(y);
+        }
+    }
+    // (opaque to the compiler from here on, or it recomputes the codes inside the loop
+    // instead of keeping them)
+#pragma unroll
+    for (int r2 = 0; r2 < VT_REGS / 2; r2++) {
+        if constexpr (HYB) {
+            asm volatile("" : "+v"(ipk[r2]));
+        } else {
+            uint32_t cw = as_u32(cpk[r2]);
+            asm volatile("" : "+v"(cw));
+            cpk[r2] = as_half2(cw);
+        }
+    }
+    // squared error of table row `row` against (s0, s1)
+    auto hyb_error = [&](int row, float s0, float s1) -> float {
+        const half2_t c = as_half2(lut[row & 511]);
+        const float c0 = (float)c.x;
+        const float c1 = (row & 512) ? -(float)c.y : (float)c.y;
+        const float e0 = c0 - s0, e1 = c1 - s1;
+        const float d0 = e0 * e0, d1 = e1 * e1;
+        return d0 + d1;
+    };
+    auto error = [&](int r, float s0) -> float {  // squared error of state r of this thread
+        if constexpr (HYB) {
+            return s_D[(ipk[r >> 1] >> (16 * (r & 1))) & 0xFFFFu];
+        } else {
+            const float e = (float)cpk[r >> 1][r & 1] - s0;
+            return e * e;
+        }
+    };
+
+    const float INF = __builtin_inff();
+    const bool constrained = overlap != nullptr;
+    const uint32_t O = constrained ? overlap[slot] : 0u;
+
+    float val[VT_REGS];
+    {
+        const float s0 = seq(0), s1 = V == 2 ? seq(1) : 0.f;
+        if constexpr (HYB) {
+#pragma unroll
+            for (int j = tid; j < 1024; j += VT_NT) s_D[j] = hyb_error(j, s0, s1);
+            __syncthreads();
+        }
+#pragma unroll
+        for (int r = 0; r < VT_REGS; r++) {
+            const uint32_t y = (uint32_t)(r * VT_NT + tid);
+            const float d = error(r, s0);
+            val[r] = (constrained && (y >> KV) != O) ? INF : d;
+        }
+        if constexpr (HYB) __syncthreads();
+    }
+
+    uint32_t *const my_ptrs = ptrs + (size_t)slot * G * PW;
+    for (int t = 1; t < G; t++) {
+        if constexpr (HYB) {
+#pragma unroll
+            for (int j = tid; j < 1024; j += VT_NT) s_D[j] = hyb_error(j, seq(V * t), seq(V * t + 1));
+        }
+        if constexpr (Geo::LOCAL) {
+            // prefix hi = NT h + tid; its predecessors p 2^OV + hi are registers p NB1 + h
+            uint32_t word[Geo::PWT];
+#pragma unroll
+            for (int w = 0; w < Geo::PWT; w++) word[w] = 0;
+#pragma unroll
+            for (int h = 0; h < NB1; h++) {
+                float bv = val[h];
+                uint32_t bp = 0;
+#pragma unroll
+                for (int p = 1; p < NC; p++) {
+                    const float v = val[p * NB1 + h];
+                    const bool lt = v < bv;
+                    bv = lt ? v : bv;
+                    bp = lt ? (uint32_t)p : bp;
+                }
+                s_best[h * VT_NT + tid] = bv;
+                word[h / Geo::FPW] |= bp << ((h % Geo::FPW) * KV);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int w = 0; w < Geo::PWT; w++) my_ptrs[(size_t)t * PW + w * VT_NT + tid] = word[w];
+        } else {
+            // prefix hi = tid % NP; this thread holds predecessors p = (VT_NT/NP) r + tid / NP
+            constexpr int Q = VT_NT / NP;
+            float bv = val[0];
+            uint32_t br = 0;
+#pragma unroll
+            for (int r = 1; r < VT_REGS; r++) {
+                const bool lt = val[r] < bv;
+                bv = lt ? val[r] : bv;
+                br = lt ? (uint32_t)r : br;
+            }
+            float *s_pv = s_best;
+            uint32_t *s_pp = reinterpret_cast<uint32_t *>(s_best + VT_NT);
+            s_pv[tid] = bv;
+            s_pp[tid] = br * Q + (uint32_t)(tid / NP);
+            __syncthreads();
+            if (tid < NP) {
+                bv = s_pv[tid];
+                uint32_t bp = s_pp[tid];
+#pragma unroll
+                for (int q = 1; q < Q; q++) {
+                    const float v = s_pv[q * NP + tid];
+                    const uint32_t p = s_pp[q * NP + tid];
+                    const bool better = v < bv || (v == bv && p < bp);
+                    bv = better ? v : bv;
+                    bp = better ? p : bp;
+                }
+                s_best[2 * VT_NT + tid] = bv;
+                my_ptrs[(size_t)t * PW + tid] = bp;
+            }
+        }
+        __syncthreads();
+        const float *best_mine = (Geo::LOCAL ? s_best : s_best + 2 * VT_NT) + (tid >> KV);
+        // (read after the barrier, so that the errors are not computed, and kept in
+        // registers that are not there, before the minima)
+        const float s0 = HYB ? 0.f : seq(t);
+        // eight states at a time: the register file has no room for 64 loads in flight
+#pragma unroll
+        for (int r0 = 0; r0 < VT_REGS; r0 += 8) {
+#pragma unroll
+            for (int r = r0; r < r0 + 8; r++) {
+                // prefix of state NT r + tid; written so that the address is one base
+                // register plus a constant
+                const float b = best_mine[r * (VT_NT >> KV)];
+                const float d = error(r, s0);
+                val[r] = b + d;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+    }
+
+    // the best allowed final state, lowest state on ties
+    float bv = INF;
+    uint32_t by = 0xFFFFFFFFu;
+#pragma unroll
+    for (int r = 0; r < VT_REGS; r++) {
+        const uint32_t y = (uint32_t)(r * VT_NT + tid);
+        const bool ok = !constrained || (y & (uint32_t)(NP - 1)) == O;
+        if (ok && val[r] < bv) {
+            bv = val[r];
+            by = y;
+        }
+    }
+    float *s_rv = s_best;
+    uint32_t *s_ry = reinterpret_cast<uint32_t *>(s_best + VT_NT);
+    s_rv[tid] = bv;
+    s_ry[tid] = by;
+    __syncthreads();
+    for (int stride = VT_NT / 2; stride > 0; stride >>= 1) {
+        if (tid < stride) {
+            const float v = s_rv[tid + stride];
+            const uint32_t y = s_ry[tid + stride];
+            if (v < s_rv[tid] || (v == s_rv[tid] && y < s_ry[tid])) {
+                s_rv[tid] = v;
+                s_ry[tid] = y;
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        final_state[slot] = s_ry[0];
+        final_value[slot] = s_rv[0];
+    }
+}
+
+// One thread per sequence walks the back-pointers from the final state.
+// pass 1: down to step G/2 - 1, whose low 16-kV bits are the overlap of Algorithm 4.
+// pass 2: the whole walk; step t contributes the top kV bits of its state as stream bits
+// t kV .. (t+1) kV - 1 (first bit = most significant bit of word 0).
+template <int KV, int V>
+__global__ __launch_bounds__(64) void viterbi_backtrace_kernel(
+    const uint32_t *__restrict__ ptrs, const uint32_t *__restrict__ final_state,
+    const float *__restrict__ final_value, int count, int pass, uint32_t *__restrict__ overlap,
+    uint32_t *__restrict__ codes, float *__restrict__ tile_err, long tile0) {
+    using Geo = VitGeo<KV>;
+    constexpr int OV = Geo::OV, NP = Geo::NP, NC = Geo::NC, PW = Geo::PW;
+    constexpr int G = VT_T / V, NWORDS = KV * G / 32;
+    const int slot = blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot >= count) return;
+    const uint32_t *my_ptrs = ptrs + (size_t)slot * G * PW;
+    uint32_t arg = final_state[slot];
+    uint32_t words[NWORDS];
+#pragma unroll
+    for (int w = 0; w < NWORDS; w++) words[w] = 0;
+    const int stop = pass == 1 ? G / 2 - 1 : 0;
+    for (int t = G - 1;; t--) {
+        if (pass == 2) {
+            const uint32_t top = arg >> OV;
+            for (int b = 0; b < KV; b++) {
+                const int pos = t * KV + b;
+                if ((top >> (KV - 1 - b)) & 1u) words[pos >> 5] |= 1u << (31 - (pos & 31));
+            }
+        }
+        if (t == stop) break;
+        const uint32_t hi = arg >> KV;
+        uint32_t p;
+        if constexpr (Geo::LOCAL) {
+            const uint32_t h = hi / VT_NT;
+            const uint32_t word = my_ptrs[(size_t)t * PW + (h / Geo::FPW) * VT_NT + (hi & (VT_NT - 1))];
+            p = (word >> ((h % Geo::FPW) * KV)) & (uint32_t)(NC - 1);
+        } else {
+            p = my_ptrs[(size_t)t * PW + hi];
+        }
+        arg = (p << OV) | hi;
+    }
+    if (pass == 1) {
+        overlap[slot] = arg & (uint32_t)(NP - 1);
+    } else {
+        uint32_t *out = codes + (size_t)(tile0 + slot) * NWORDS;
+#pragma unroll
+        for (int w = 0; w < NWORDS; w++) out[w] = words[w];
+        if (tile_err) tile_err[tile0 + slot] = final_value[slot];
+    }
+}
+
+// Workspace for `tiles` sequences in flight: three words per sequence (final state,
+// overlap, final value), then the back-pointers.
+template <int KV, int V>
+constexpr size_t per_tile_bytes() {
+    return (size_t)(VT_T / V) * VitGeo<KV>::PW * sizeof(uint32_t);
+}
+constexpr size_t VT_HEAD_ALIGN = 256;
+
+size_t head_bytes(long tiles) {
+    const size_t b = (size_t)tiles * 3 * sizeof(uint32_t);
+    return (b + VT_HEAD_ALIGN - 1) / VT_HEAD_ALIGN * VT_HEAD_ALIGN;
+}
+
+template <int KV, int V, int CODE>
+hipError_t quantize_gpu_t(const float *W, int m, int n, const uint32_t *lut, uint32_t *codes,
+                          float *tile_err, void *ws, size_t ws_bytes, hipStream_t st) {
+    const int tn = n / 16;
+    const long ntiles = (long)(m / 16) * tn;
+    // the largest batch the workspace holds
+    long cap = (long)(ws_bytes / per_tile_bytes<KV, V>());  // upper bound, trimmed below
+    if (cap > ntiles) cap = ntiles;
+    while (cap > 0 && head_bytes(cap) + (size_t)cap * per_tile_bytes<KV, V>() > ws_bytes) cap--;
+    if (cap <= 0) return hipErrorInvalidValue;
+    uint32_t *final_state = (uint32_t *)ws;
+    uint32_t *overlap = final_state + cap;
+    float *final_value = (float *)(overlap + cap);
+    uint32_t *ptrs = (uint32_t *)((char *)ws + head_bytes(cap));
+    for (long tile0 = 0; tile0 < ntiles; tile0 += cap) {
+        const int cnt = (int)(ntiles - tile0 < cap ? ntiles - tile0 : cap);
+        const dim3 bgrid((cnt + 63) / 64);
+        hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, n, tn,
+                           tile0, lut, 1, (const uint32_t *)nullptr, ptrs, final_state, final_value);
+        hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V>), bgrid, dim3(64), 0, st, ptrs, final_state,
+                           final_value, cnt, 1, overlap, codes, tile_err, tile0);
+        hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, n, tn,
+                           tile0, lut, 0, (const uint32_t *)overlap, ptrs, final_state, final_value);
+        hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V>), bgrid, dim3(64), 0, st, ptrs, final_state,
+                           final_value, cnt, 2, overlap, codes, tile_err, tile0);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
+size_t quantize_gpu_workspace(int k, int V, long tiles) {
+    const int kV = k * V;
+    size_t pw;
+    switch (kV) {
+        case 2: pw = VitGeo<2>::PW; break;
+        case 3: pw = VitGeo<3>::PW; break;
+        case 4: pw = VitGeo<4>::PW; break;
+        case 6: pw = VitGeo<6>::PW; break;
+        default: pw = VitGeo<8>::PW; break;
+    }
+    return head_bytes(tiles) + (size_t)tiles * (VT_T / V) * pw * sizeof(uint32_t);
+}
+
+hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, const uint32_t *lut,
+                               uint32_t *codes, float *tile_err, void *ws, size_t ws_bytes,
+                               hipStream_t st) {
+    if (code_id == CODE_HYB) {
+        if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<8, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+    } else if (code_id == CODE_3INST) {
+        if (k == 2) return quantize_gpu_t<2, 1, CODE_3INST>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<3, 1, CODE_3INST>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<4, 1, CODE_3INST>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+    } else {
+        if (k == 2) return quantize_gpu_t<2, 1, CODE_1MAD>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<3, 1, CODE_1MAD>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<4, 1, CODE_1MAD>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+    }
+}
+
+}  // namespace qtip
