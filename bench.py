@@ -40,6 +40,79 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def bench_quantize(args, q, torch, np):
+    """The GPU tail-biting Viterbi quantizer on a 2048 x 2048 matrix of i.i.d. Gaussian
+    weights scaled to the code (16384 tiles), 2-bit 3INST: one step = the whole matrix.
+    The rate is in trellis state updates: per tile 2 passes (Algorithm 4) x 256 steps x
+    2^16 states.  ALU roof: an update is four dependent binary32 operations that cannot be
+    fused (subtract, multiply, add, compare-for-minimum), against 256 CUs x 4 SIMDs x 16
+    lanes x 2.4 GHz single operations per second."""
+    import qtip_synth as synth
+    code_id, k, V, m, n = synth.CODE_3INST, 2, 1, 2048, 2048
+    steps = max(1, min(args.steps, 3))
+    warmup = max(1, min(args.warmup, 1))
+    ntiles = (m // 16) * (n // 16)
+    rng = np.random.default_rng(240611235 + 77)
+    sd = 1.2437                                  # standard deviation of the 3INST code values
+    Wh = (rng.standard_normal((m, n)) * sd).astype(np.float32)
+    W = torch.from_numpy(Wh).cuda()
+    in_flight = 4096
+    ws_bytes = q.qtip_quantize_gpu_workspace(k, V, in_flight)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    codes = torch.zeros((ntiles, 8 * k), dtype=torch.int32, device="cuda")
+    err = torch.zeros(ntiles, dtype=torch.float32, device="cuda")
+    run = lambda: q.qtip_quantize_gpu(W, m, n, 16, k, V, code_id, None, codes, err, ws, ws_bytes)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    updates = ntiles * 2 * 256 * 65536
+    rate = updates / (ms * 1e-3)
+    mse = float(err.double().sum()) / (m * n)
+    log(f"quantize: {ms:.1f} ms per {m}x{n} matrix = {ms*1e3/ntiles:.2f} us/tile, "
+        f"{rate/1e12:.2f} T state updates/s, mse/var {mse/sd**2:.4f}")
+    peak = 256 * 4 * 16 * 2.4e9
+    roofline = {"bound": "alu", "kernel": "viterbi_forward_kernel", "unit": "T single fp32 operations/s",
+                "achieved": 4 * rate / 1e12, "peak": peak / 1e12, "frac": 4 * rate / peak,
+                "traffic": None, "operations_per_state_update": 4,
+                "frac_of_published_fp32_vector_peak_157.3": 4 * rate / 157.3e12}
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        C = oracle.codebook(16, V, code_id)
+        codes_h = codes.cpu().numpy().view(np.uint32)
+        t0 = time.perf_counter()
+        done = 0
+        same = 0
+        while time.perf_counter() - t0 < 10.0 and done < 64:
+            S = Wh[0:16, 16 * done:16 * done + 16].reshape(-1)
+            d, words = oracle.tailbiting_quantize_f32(S, 16, k, V, C)
+            same += int(np.array_equal(words, codes_h[done]))
+            done += 1
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": done * 2 * 256 * 65536 / dt, "unit": "state updates/s", "cores": 1,
+                        "kind": "oracle",
+                        "sample": f"first {done} tiles of the matrix, binary32 Algorithm 4 of the "
+                                  f"oracle, {dt:.1f} s; {same} of {done} streams equal the GPU's",
+                        "tiles_per_s": done / dt}
+        log(f"cpu oracle: {done/dt:.2f} tiles/s on one thread; {same}/{done} streams identical")
+    return {"metric": "tail-biting Viterbi quantization (L=16, 2-bit 3INST, T=256), trellis state "
+                      "updates per second",
+            "value": rate, "unit": "state updates/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"quantize_3inst_k2_{m}x{n}", "m": m, "n": n, "code": "3INST",
+                       "L": 16, "k": k, "V": V, "tiles": ntiles, "tiles_in_flight": in_flight},
+            "us_per_tile": ms * 1e3 / ntiles, "mse_over_variance": mse / sd ** 2,
+            "roofline": roofline, "cpu_baseline": cpu_baseline}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +126,9 @@ def main():
                          "traffic to scale the counters by")
     ap.add_argument("--all", action="store_true",
                     help="also time every configured workload (report on stderr)")
+    ap.add_argument("--quantize", action="store_true",
+                    help="instead of the inference path, time the GPU quantizer "
+                         "(qtip_quantize_gpu) and print its JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -69,6 +145,10 @@ def main():
     torch.cuda.set_device(0)
     q.lib()
     dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    if args.quantize:
+        print(json.dumps(bench_quantize(args, q, torch, np)), flush=True)
+        return
 
     def prepare(w, min_total=512 << 20):
         inp = synth.make_inputs(w)

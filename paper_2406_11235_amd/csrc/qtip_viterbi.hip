@@ -61,6 +61,39 @@ struct VitGeo {
 
 __host__ __device__ constexpr int vit_max(int a, int b) { return a > b ? a : b; }
 
+// Minimum of val[base + j stride], j = 0 .. COUNT-1, and the lowest j that attains it.
+// CH independent compare-select chains (j = c mod CH) run interleaved, so that the wait
+// states between a compare and the selects reading its mask are filled, and are merged
+// at the end; ties go to the lower j at every stage.  All indices fold to constants once
+// the callers' loops are unrolled.
+template <int COUNT, int CH>
+__device__ __forceinline__ void argmin_regs(const float (&val)[VT_REGS], int base, int stride, float &bv,
+                                            uint32_t &bj) {
+    float cv[CH];
+    uint32_t cj[CH];
+#pragma unroll
+    for (int c = 0; c < CH; c++) {
+        cv[c] = val[base + c * stride];
+        cj[c] = (uint32_t)c;
+    }
+#pragma unroll
+    for (int j = CH; j < COUNT; j++) {
+        const int c = j % CH;
+        const float v = val[base + j * stride];
+        const bool lt = v < cv[c];
+        cv[c] = lt ? v : cv[c];
+        cj[c] = lt ? (uint32_t)j : cj[c];
+    }
+    bv = cv[0];
+    bj = cj[0];
+#pragma unroll
+    for (int c = 1; c < CH; c++) {
+        const bool better = cv[c] < bv || (cv[c] == bv && cj[c] < bj);
+        bv = better ? cv[c] : bv;
+        bj = better ? cj[c] : bj;
+    }
+}
+
 // rotate = 1: the sequence rotated by T/2 (Algorithm 4's first call).  overlap != null:
 // the first state's top 16-kV bits and the last state's low 16-kV bits are forced to
 // overlap[slot] (its second call).  Sequence `slot` of the batch is tile tile0 + slot.
@@ -176,32 +209,23 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
             for (int w = 0; w < Geo::PWT; w++) word[w] = 0;
 #pragma unroll
             for (int h = 0; h < NB1; h++) {
-                float bv = val[h];
-                uint32_t bp = 0;
-#pragma unroll
-                for (int p = 1; p < NC; p++) {
-                    const float v = val[p * NB1 + h];
-                    const bool lt = v < bv;
-                    bv = lt ? v : bv;
-                    bp = lt ? (uint32_t)p : bp;
-                }
+                float bv;
+                uint32_t bp;
+                argmin_regs<NC, (NB1 >= 4 || NC < 8) ? 1 : 4 / NB1>(val, h, NB1, bv, bp);
                 s_best[h * VT_NT + tid] = bv;
                 word[h / Geo::FPW] |= bp << ((h % Geo::FPW) * KV);
-                __builtin_amdgcn_sched_barrier(0);
+                // a few chains at a time: enough to fill the wait states between a compare
+                // and the selects that use its mask, few enough to stay in registers
+                if ((h & 3) == 3) __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int w = 0; w < Geo::PWT; w++) my_ptrs[(size_t)t * PW + w * VT_NT + tid] = word[w];
         } else {
             // prefix hi = tid % NP; this thread holds predecessors p = (VT_NT/NP) r + tid / NP
             constexpr int Q = VT_NT / NP;
-            float bv = val[0];
-            uint32_t br = 0;
-#pragma unroll
-            for (int r = 1; r < VT_REGS; r++) {
-                const bool lt = val[r] < bv;
-                bv = lt ? val[r] : bv;
-                br = lt ? (uint32_t)r : br;
-            }
+            float bv;
+            uint32_t br;
+            argmin_regs<VT_REGS, 4>(val, 0, 1, bv, br);
             float *s_pv = s_best;
             uint32_t *s_pp = reinterpret_cast<uint32_t *>(s_best + VT_NT);
             s_pv[tid] = bv;

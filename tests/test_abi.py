@@ -80,11 +80,24 @@ def test_argument_errors_need_no_gpu(q):
         (L.qtip_quantize(p, 16, 16, 16, 2, 2, 2, None, p, None), EINVAL),
         (L.qtip_quantize(p, 16, 16, 16, 6, 1, 1, None, p, None), EUNSUP),
         (L.qtip_quantize(p, 16, 20, 16, 2, 1, 1, None, p, None), EINVAL),
+        (L.qtip_quantize_gpu(None, 16, 16, 16, 2, 1, 1, None, p, None, 256, 1 << 21, None), EINVAL),
+        (L.qtip_quantize_gpu(p, 16, 16, 16, 2, 1, 1, None, p, None, None, 1 << 21, None), EINVAL),
+        (L.qtip_quantize_gpu(p, 16, 16, 16, 2, 1, 1, None, p, None, 256, 1000, None), EINVAL),
+        (L.qtip_quantize_gpu(p, 16, 16, 16, 2, 1, 1, None, p, None, 260, 1 << 21, None), EINVAL),
+        (L.qtip_quantize_gpu(p, 16, 16, 16, 2, 2, 2, None, p, None, 256, 1 << 21, None), EINVAL),
+        (L.qtip_quantize_gpu(p, 16, 16, 12, 2, 1, 1, None, p, None, 256, 1 << 21, None), EUNSUP),
+        (L.qtip_quantize_gpu(p, 16, 16, 16, 2, 2, 1, None, p, None, 256, 1 << 21, None), EUNSUP),
+        (L.qtip_quantize_gpu(p, 16, 20, 16, 2, 1, 1, None, p, None, 256, 1 << 21, None), EINVAL),
     ]
     for i, (rc, want) in enumerate(cases):
         assert rc == want, (i, rc, want, q.qtip_last_error())
     assert "multiples of 16" in q.qtip_last_error()
     assert L.qtip_decode_states(p, 0, 16, 1, 0, None, p, None) == 0     # empty input: no launch
+    # workspace sizes: about 1 MiB of back-pointers per tile at V = 1, monotone in tiles
+    w1, w2 = q.qtip_quantize_gpu_workspace(2, 1, 1), q.qtip_quantize_gpu_workspace(2, 1, 2)
+    assert 1 << 20 <= w1 <= (1 << 20) + 4096 and w1 < w2 <= 2 * w1
+    assert q.qtip_quantize_gpu_workspace(4, 2, 1) < w1
+    assert q.qtip_quantize_gpu_workspace(1, 1, 1) == 0 and q.qtip_quantize_gpu_workspace(2, 1, 0) == 0
 
 
 def test_binding_raises_with_message(q):
