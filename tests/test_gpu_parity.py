@@ -160,6 +160,30 @@ def test_matmat_large_batch_staged_activations(q, code_id, k, V, m, n, B):
     assert np.array_equal(run_matmat(q, w, inp), got)  # fixed summation order
 
 
+def test_stacked_matrices_are_one_launch(q):
+    """Matrices that share an input (q/k/v, up/gate: the matrix fusion of the paper's
+    generation-speed runs) are stacked along the rows: tile rows are independent and contiguous in the code buffer, so the
+    concatenated buffers are one valid matrix and one launch gives the concatenated outputs."""
+    n = 2064
+    parts, refs = [], []
+    X = None
+    for sub, m in enumerate((64, 16, 112)):
+        w = small_workload(CODE_3INST, 2, 1, m, n, sub=40 + sub)
+        inp = synth.make_inputs(w)
+        X = inp.X if X is None else X
+        inp.X = X
+        parts.append(inp.codes)
+        refs.append(run_matmat(q, w, inp, use_matvec=True, scale=False))
+    w = small_workload(CODE_3INST, 2, 1, 192, n)
+    inp = synth.make_inputs(w)
+    inp.codes = np.concatenate(parts, axis=0)
+    inp.X = X
+    got = run_matmat(q, w, inp, use_matvec=True, scale=False)
+    assert np.array_equal(got, np.concatenate(refs, axis=1))
+    Wref = oracle.dequantize(inp.codes, 16, 2, 1, CODE_3INST, 192, n, None)
+    assert rel_err(got, oracle.matmat_dense(Wref, X)) <= OBSERVED_TOL
+
+
 FULL = ["cfg1_3inst_k2_1024x1024", "cfg2_3inst_k2_4096x4096", "cfg3_1mad_k2_14336x4096",
         "cfg3_1mad_k3_14336x4096", "cfg3_1mad_k4_14336x4096", "cfg3_1mad_k2_4096x14336",
         "cfg3_1mad_k3_4096x14336", "cfg3_1mad_k4_4096x14336", "cfg4_hyb_k2_8192x28672",
