@@ -85,6 +85,10 @@ def lib():
         L.orc_viterbi_f32.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp]
         L.orc_tailbiting_quantize_f32.restype = c.c_float
         L.orc_tailbiting_quantize_f32.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.orc_block_ldl.restype = i32
+        L.orc_block_ldl.argtypes = [vp, i32, i32, vp, vp]
+        L.orc_ldlq_feedback_f32.restype = None
+        L.orc_ldlq_feedback_f32.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
         L.orc_stream_distortion.restype = dbl
         L.orc_stream_distortion.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         L.orc_exhaustive_tailbiting.restype = dbl
@@ -316,3 +320,52 @@ def exhaustive_walk(S, L, k, V, C):
     S = _f64(S)
     C = _f64(C).reshape(1 << L, V)
     return float(lib().orc_exhaustive_walk(_p(S), S.size, L, k, V, _p(C)))
+
+
+def block_ldl(H, g=16):
+    """H = L D L^T, L unit block lower triangular, D block diagonal: returns (L, D blocks)."""
+    H = _f64(H)
+    n = H.shape[0]
+    assert H.shape == (n, n) and n % g == 0
+    Lm = np.zeros((n, n), dtype=np.float64)
+    D = np.zeros((n // g, g, g), dtype=np.float64)
+    rc = lib().orc_block_ldl(_p(H), n, g, _p(Lm), _p(D))
+    assert rc == 0, rc
+    return Lm, D
+
+
+def ldlq_feedback_f32(W, E, A, j, g=16):
+    W, E, A = _f32(W), _f32(E), _f32(A)
+    m, n = W.shape
+    x = np.zeros((m, g), dtype=np.float32)
+    lib().orc_ldlq_feedback_f32(_p(W), _p(E), _p(A), m, n, g, j, _p(x))
+    return x
+
+
+def ldlq_quantize_f32(W, A, L, k, V, code_id, lut=None, rounder=None):
+    """Algorithm 5 with T_x = T_y = 16: column blocks from the last to the first, feedback in
+    binary32 (ldlq_feedback_f32), every 16x16 block of x rounded as one sequence by the
+    binary32 tail-biting quantizer.  Returns (codes (tiles, 8k), What float32, x of every block).
+    `rounder(S) -> (value, words)` replaces the quantizer (tests)."""
+    W, A = _f32(W), _f32(A)
+    m, n = W.shape
+    tn = n // 16
+    C = codebook(L, V, code_id, lut)
+    codes = np.zeros(((m // 16) * tn, 8 * k), dtype=np.uint32)
+    What = np.zeros((m, n), dtype=np.float32)
+    E = np.zeros((m, n), dtype=np.float32)
+    xs = np.zeros((m, n), dtype=np.float32)
+    for j in range(tn - 1, -1, -1):
+        x = ldlq_feedback_f32(W, E, A, j)
+        xs[:, 16 * j:16 * j + 16] = x
+        for I in range(m // 16):
+            S = x[16 * I:16 * I + 16, :].reshape(-1)
+            if rounder is None:
+                _, words = tailbiting_quantize_f32(S, L, k, V, C)
+            else:
+                _, words = rounder(S)
+            codes[I * tn + j] = words
+            vals, _ = decode_sequence_table(words, 256, L, k, V, C)
+            What[16 * I:16 * I + 16, 16 * j:16 * j + 16] = vals.reshape(16, 16).astype(np.float32)
+        E[:, 16 * j:16 * j + 16] = W[:, 16 * j:16 * j + 16] - What[:, 16 * j:16 * j + 16]
+    return codes, What, xs

@@ -22,7 +22,9 @@
  *   - the Viterbi algorithm on the bitshift trellis (Section 2.3), the
  *     tail-biting approximation (Algorithm 4) and exhaustive searches for
  *     tiny problems; the same two in binary32, operation by operation, for
- *     checking a single-precision quantizer decision by decision.
+ *     checking a single-precision quantizer decision by decision;
+ *   - the quantizer's outer loop, BlockLDLQ with the trellis quantizer as its
+ *     rounder (Algorithm 5): block LDL decomposition and the feedback step.
  *
  * Storage convention (the paper fixes only the logical bit order, through
  * Figure 1: the first stored bit is the most significant bit of the first
@@ -640,3 +642,109 @@ double orc_exhaustive_walk(const double *S, int T, int L, int k, int V, const do
     }
     return best;
 }
+
+/* --------------------------------------------------- BlockLDLQ (Algorithm 5) */
+
+/*
+ * g-block LDL decomposition of a symmetric positive definite H (Algorithm 5,
+ * second line, g = T_y): H = L D L^T with L unit block lower triangular
+ * (identity g x g blocks on its diagonal) and D block diagonal.  Plain
+ * right-looking elimination in binary64: D_j is the current diagonal block,
+ * L_ij = S_ij D_j^-1 below it, and the trailing matrix loses L_ij D_j L_kj^T.
+ * D_j^-1 by Gauss-Jordan with row pivoting.  H, L: n x n row-major (L full,
+ * zeros above the diagonal blocks); D: (n/g) blocks of g x g.  0 or -1.
+ */
+int orc_block_ldl(const double *H, int n, int g, double *Lout, double *Dout) {
+    if (n % g) return -1;
+    int nb = n / g;
+    double *S = (double *)malloc(sizeof(double) * (size_t)n * n);
+    double *inv = (double *)malloc(sizeof(double) * (size_t)g * g);
+    double *aug = (double *)malloc(sizeof(double) * (size_t)g * 2 * g);
+    if (!S || !inv || !aug) {
+        free(S);
+        free(inv);
+        free(aug);
+        return -1;
+    }
+    memcpy(S, H, sizeof(double) * (size_t)n * n);
+    memset(Lout, 0, sizeof(double) * (size_t)n * n);
+    for (int i = 0; i < n; i++) Lout[(size_t)i * n + i] = 1.0;
+    for (int j = 0; j < nb; j++) {
+        int o = j * g;
+        for (int r = 0; r < g; r++)
+            for (int c = 0; c < g; c++) {
+                double v = S[(size_t)(o + r) * n + o + c];
+                Dout[((size_t)j * g + r) * g + c] = v;
+                aug[r * 2 * g + c] = v;
+                aug[r * 2 * g + g + c] = r == c ? 1.0 : 0.0;
+            }
+        for (int c = 0; c < g; c++) {
+            int piv = c;
+            for (int r = c + 1; r < g; r++)
+                if (fabs(aug[r * 2 * g + c]) > fabs(aug[piv * 2 * g + c])) piv = r;
+            if (aug[piv * 2 * g + c] == 0.0) {
+                free(S);
+                free(inv);
+                free(aug);
+                return -1;
+            }
+            if (piv != c)
+                for (int q = 0; q < 2 * g; q++) {
+                    double t = aug[c * 2 * g + q];
+                    aug[c * 2 * g + q] = aug[piv * 2 * g + q];
+                    aug[piv * 2 * g + q] = t;
+                }
+            double d = aug[c * 2 * g + c];
+            for (int q = 0; q < 2 * g; q++) aug[c * 2 * g + q] /= d;
+            for (int r = 0; r < g; r++) {
+                if (r == c) continue;
+                double f = aug[r * 2 * g + c];
+                for (int q = 0; q < 2 * g; q++) aug[r * 2 * g + q] -= f * aug[c * 2 * g + q];
+            }
+        }
+        for (int r = 0; r < g; r++)
+            for (int c = 0; c < g; c++) inv[r * g + c] = aug[r * 2 * g + g + c];
+        /* L_ij = S_ij D_j^-1 for the rows below the block */
+        for (int i = o + g; i < n; i++)
+            for (int c = 0; c < g; c++) {
+                double acc = 0.0;
+                for (int q = 0; q < g; q++) acc += S[(size_t)i * n + o + q] * inv[q * g + c];
+                Lout[(size_t)i * n + o + c] = acc;
+            }
+        /* trailing update: S_ik -= L_ij D_j L_kj^T = L_ij (S_kj)^T (D_j symmetric) */
+#pragma omp parallel for schedule(static)
+        for (int i = o + g; i < n; i++)
+            for (int kk = o + g; kk < n; kk++) {
+                double acc = 0.0;
+                for (int q = 0; q < g; q++) acc += Lout[(size_t)i * n + o + q] * S[(size_t)kk * n + o + q];
+                S[(size_t)i * n + kk] -= acc;
+            }
+    }
+    free(S);
+    free(inv);
+    free(aug);
+    return 0;
+}
+
+/*
+ * The feedback step of Algorithm 5 for column block j (g = T_y columns):
+ *   x = W[:, jg:(j+1)g] + (W - What)[:, (j+1)g:] A[(j+1)g:, jg:(j+1)g]
+ * (A = L - I is zero on and above its diagonal blocks, so the block's own
+ * columns drop out of the paper's slice jT_y: ).  Binary32, in one fixed
+ * order so that a GPU implementation can be followed decision by decision:
+ * start from W[r][jg+c] and add the terms E[r][i] * A[i][jg+c] for
+ * i = (j+1)g ... n-1 in ascending order, each with one fused multiply-add.
+ * E = W - What (m x n), A n x n, x m x g, all row-major float.
+ */
+void orc_ldlq_feedback_f32(const float *W, const float *E, const float *A, int m, int n, int g,
+                           int j, float *x) {
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < m; r++)
+        for (int c = 0; c < g; c++) {
+            float acc = W[(size_t)r * n + j * g + c];
+            for (int i = (j + 1) * g; i < n; i++)
+                acc = fmaf(E[(size_t)r * n + i], A[(size_t)i * n + j * g + c], acc);
+            x[(size_t)r * g + c] = acc;
+        }
+}
+

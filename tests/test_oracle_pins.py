@@ -497,3 +497,115 @@ def test_tailbiting_f32_stream_is_cyclic_and_close_to_f64():
         same += int(np.array_equal(w32, w64))
         assert true <= d64 * 1.05                     # a near-tie may pick another overlap
     assert same >= 4
+
+
+# ------------------------------------------------------- BlockLDLQ (Algorithm 5)
+
+def _random_spd(rng, n, samples=None, corr=0.9):
+    """A proxy-Hessian-like matrix: second moment of strongly correlated Gaussian inputs."""
+    samples = samples or 4 * n
+    base = rng.standard_normal((samples, 1))
+    X = corr * base + (1 - corr) * rng.standard_normal((samples, n))
+    X = X * rng.uniform(0.5, 2.0, n)[None, :]
+    return X.T @ X / samples + 1e-3 * np.eye(n)
+
+
+@pytest.mark.parametrize("n,g", [(64, 16), (48, 8), (32, 16)])
+def test_block_ldl_against_cholesky(n, g):
+    rng = np.random.default_rng(n + g)
+    H = _random_spd(rng, n)
+    Lm, D = oracle.block_ldl(H, g)
+    nb = n // g
+    Dfull = np.zeros((n, n))
+    for j in range(nb):
+        Dfull[j * g:(j + 1) * g, j * g:(j + 1) * g] = D[j]
+        assert np.array_equal(Lm[j * g:(j + 1) * g, j * g:(j + 1) * g], np.eye(g))   # unit blocks
+        assert np.all(Lm[j * g:(j + 1) * g, (j + 1) * g:] == 0)                       # block lower
+        assert np.allclose(D[j], D[j].T, atol=1e-12) and np.all(np.linalg.eigvalsh(D[j]) > 0)
+    assert np.allclose(Lm @ Dfull @ Lm.T, H, rtol=1e-10, atol=1e-12)
+    # the same factors from a library Cholesky: H = R R^T, L = R blockdiag(R_jj)^-1, D_j = R_jj R_jj^T
+    R = np.linalg.cholesky(H)
+    for j in range(nb):
+        Rjj = R[j * g:(j + 1) * g, j * g:(j + 1) * g]
+        assert np.allclose(D[j], Rjj @ Rjj.T, rtol=1e-9, atol=1e-12)
+        assert np.allclose(Lm[:, j * g:(j + 1) * g], R[:, j * g:(j + 1) * g] @ np.linalg.inv(Rjj),
+                           rtol=1e-8, atol=1e-10)
+
+
+def test_ldlq_feedback_is_the_stated_sum():
+    rng = np.random.default_rng(12)
+    m, n, g = 32, 80, 16
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    E = rng.standard_normal((m, n)).astype(np.float32)
+    A = rng.standard_normal((n, n)).astype(np.float32)      # junk on and above the diagonal blocks
+    for j in range(n // g):
+        x = oracle.ldlq_feedback_f32(W, E, A, j, g)
+        lo = (j + 1) * g
+        want = W[:, j * g:lo].astype(np.float64) + E[:, lo:].astype(np.float64) @ A[lo:, j * g:lo].astype(np.float64)
+        assert np.allclose(x, want, rtol=2e-5, atol=2e-5)
+    assert np.array_equal(oracle.ldlq_feedback_f32(W, E, A, n // g - 1, g), W[:, n - g:])  # last block: no feedback
+    # exactly representable inputs: the binary32 sum is the exact sum, whatever the order
+    Wi = rng.integers(-4, 5, (m, n)).astype(np.float32)
+    Ei = rng.integers(-4, 5, (m, n)).astype(np.float32)
+    Ai = (rng.integers(-4, 5, (n, n)) / 8.0).astype(np.float32)
+    x = oracle.ldlq_feedback_f32(Wi, Ei, Ai, 1, g)
+    assert np.array_equal(x, (Wi[:, g:2 * g] + Ei[:, 2 * g:].astype(np.float64) @ Ai[2 * g:, g:2 * g]).astype(np.float32))
+    # one fused multiply-add per term, ascending: repeated with numpy's float64 products
+    # rounded once (an fma of binary32 operands is the binary64 product and sum rounded once,
+    # as long as the binary64 sum is exact enough: checked on a short row)
+    r, c = 3, 5
+    acc = np.float32(W[r, c])
+    for i in range(g, n):
+        acc = np.float32(np.float64(E[r, i]) * np.float64(A[i, c]) + np.float64(acc))
+    assert abs(float(oracle.ldlq_feedback_f32(W, E, A, 0, g)[r, c]) - float(acc)) <= 2e-6 * abs(float(acc)) + 1e-6
+
+
+def test_ldlq_loop_identities():
+    """With any rounder, Algorithm 5 satisfies (W - What) L = x - What block by block, which is
+    what turns the proxy loss into a sum over blocks: tr(E H E^T) = sum_j tr(eta_j D_j eta_j^T)."""
+    rng = np.random.default_rng(21)
+    m, n = 16, 64
+    L, k, V = 8, 2, 1
+    H = _random_spd(rng, n)
+    Lm, D = oracle.block_ldl(H, 16)
+    A = (Lm - np.eye(n)).astype(np.float32)
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    C8 = rng.standard_normal((1 << L, V)).astype(np.float16).astype(np.float64)
+
+    def rounder(S):
+        return oracle.tailbiting_quantize_f32(S, L, k, V, C8)
+
+    import oracle as o
+    orig = o.codebook
+    try:
+        o.codebook = lambda *a, **kw: C8                     # a table code at L = 8 keeps this fast
+        codes, What, xs = o.ldlq_quantize_f32(W, A, L, k, V, CODE_3INST, rounder=rounder)
+    finally:
+        o.codebook = orig
+    E = W.astype(np.float64) - What
+    eta = xs.astype(np.float64) - What
+    assert np.allclose(E @ (np.eye(n) + A.astype(np.float64)), eta, rtol=1e-4, atol=1e-4)
+    proxy = np.trace(E @ H @ E.T)
+    blocks = sum(np.trace(eta[:, 16 * j:16 * j + 16] @ D[j] @ eta[:, 16 * j:16 * j + 16].T) for j in range(n // 16))
+    assert abs(proxy - blocks) <= 1e-3 * proxy
+    # every block of What is the decode of its own stream
+    for j in range(n // 16):
+        vals, _ = oracle.decode_sequence_table(codes[j], 256, L, k, V, C8)
+        assert np.array_equal(What[:, 16 * j:16 * j + 16], vals.reshape(16, 16).astype(np.float32))
+
+
+def test_ldlq_without_correlation_is_plain_quantization_and_feedback_helps():
+    rng = np.random.default_rng(33)
+    m, n = 16, 64
+    C = oracle.codebook(16, 1, CODE_3INST)
+    W = (rng.standard_normal((m, n)) * C.std()).astype(np.float32)
+    zero = np.zeros((n, n), dtype=np.float32)
+    codes0, What0, _ = oracle.ldlq_quantize_f32(W, zero, 16, 2, 1, CODE_3INST)
+    for j in range(n // 16):
+        _, words = oracle.tailbiting_quantize_f32(W[:, 16 * j:16 * j + 16].reshape(-1), 16, 2, 1, C)
+        assert np.array_equal(codes0[j], words)
+    H = _random_spd(rng, n, corr=0.95)
+    Lm, _ = oracle.block_ldl(H, 16)
+    codes1, What1, _ = oracle.ldlq_quantize_f32(W, (Lm - np.eye(n)).astype(np.float32), 16, 2, 1, CODE_3INST)
+    loss = lambda Wh: np.trace((Wh - W).astype(np.float64) @ H @ (Wh - W).astype(np.float64).T)
+    assert loss(What1) < 0.8 * loss(What0)               # Section 2.1: feedback lowers the proxy loss
