@@ -166,6 +166,44 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
                       const void *lut_f16, uint32_t *codes_out, float *tile_err, void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/*
+ * Block LDL decomposition of a proxy Hessian (Algorithm 5, second and third lines, with
+ * T_y = 16): H = L D L^T, L unit block lower triangular with 16x16 identity blocks on
+ * its diagonal, D block diagonal; the feedback matrix is A = L - I.
+ *   H:       device, n x n row-major binary64, symmetric positive definite (only its
+ *            lower triangle is read).  If it is not positive definite the results
+ *            hold non-finite values; no error is raised.
+ *   A_out:   device, n x n row-major fp32: L - I (zero on and above the diagonal blocks).
+ *   D_out:   device, (n/16) x 16 x 16 binary64, or NULL: the diagonal blocks of D.
+ *   workspace: device, 256-byte aligned, qtip_block_ldl_workspace(n) bytes (two n x n
+ *            binary64 matrices); contents are scratch.
+ * Binary64 throughout; 2 n/16 + 2 kernel launches on `stream`, no synchronization.
+ */
+size_t qtip_block_ldl_workspace(int n);
+int qtip_block_ldl(const double *H, int n, float *A_out, double *D_out, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
+/*
+ * The quantizer inside BlockLDLQ (Algorithm 5 with T_x = T_y = 16): for column blocks j
+ * from the last to the first,
+ *     x = W[:, 16j:16j+16] + (W - What)[:, 16j+16:] A[16j+16:, 16j:16j+16],
+ * every 16x16 block of x quantized as one sequence by the tail-biting Viterbi quantizer
+ * (as qtip_quantize_gpu, same arithmetic), What[:, 16j:16j+16] = its decode.
+ *   W: device m x n fp32.  A: device n x n fp32 from qtip_block_ldl (only the blocks
+ *   below the diagonal blocks are read).  codes_out: as qtip_quantize_gpu.
+ *   What_out: device m x n fp32 or NULL: the decoded weights.  tile_err: device,
+ *   (m/16)*(n/16) floats or NULL: squared error of every tile against its x.
+ *   workspace: 256-byte aligned; qtip_quantize_ldlq_workspace(m, n, k, V, t) bytes keep
+ *   t tiles of a column block in flight (a block has m/16 tiles; t = m/16 is the most
+ *   that helps; any t >= 1 works).
+ * The feedback sum is binary32, terms added in ascending column order with one fused
+ * multiply-add each, so that the input of the quantizer is reproducible.
+ */
+size_t qtip_quantize_ldlq_workspace(int m, int n, int k, int V, long tiles);
+int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int k, int V, int code_id,
+                       const void *lut_f16, uint32_t *codes_out, float *What_out, float *tile_err,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Message for the last error on this thread ("" if none). Never NULL. */
 const char *qtip_last_error(void);
 

@@ -18,7 +18,9 @@ _lib = None
 
 EXPORTS = ["qtip_rht", "qtip_rht_f32", "qtip_decode_matvec", "qtip_decode_matmat",
            "qtip_dequantize", "qtip_decode_states", "qtip_quantize",
-           "qtip_quantize_gpu_workspace", "qtip_quantize_gpu", "qtip_last_error", "qtip_version"]
+           "qtip_quantize_gpu_workspace", "qtip_quantize_gpu", "qtip_block_ldl_workspace",
+           "qtip_block_ldl", "qtip_quantize_ldlq_workspace", "qtip_quantize_ldlq", "qtip_last_error",
+           "qtip_version"]
 
 
 class QtipError(RuntimeError):
@@ -68,6 +70,15 @@ def lib():
         L.qtip_quantize_gpu.restype = i32
         L.qtip_quantize_gpu.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp,
                                         c.c_size_t, vp]
+        L.qtip_block_ldl_workspace.restype = c.c_size_t
+        L.qtip_block_ldl_workspace.argtypes = [i32]
+        L.qtip_block_ldl.restype = i32
+        L.qtip_block_ldl.argtypes = [vp, i32, vp, vp, vp, c.c_size_t, vp]
+        L.qtip_quantize_ldlq_workspace.restype = c.c_size_t
+        L.qtip_quantize_ldlq_workspace.argtypes = [i32, i32, i32, i32, c.c_long]
+        L.qtip_quantize_ldlq.restype = i32
+        L.qtip_quantize_ldlq.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp,
+                                         c.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -160,3 +171,23 @@ def qtip_quantize_gpu(W, m, n, L, k, V, code_id, lut, codes_out, tile_err, works
     return _check(lib().qtip_quantize_gpu(_ptr(W), m, n, L, k, V, code_id, _ptr(lut),
                                           _ptr(codes_out), _ptr(tile_err), _ptr(workspace),
                                           workspace_bytes, _stream(stream)))
+
+
+def qtip_block_ldl_workspace(n):
+    return int(lib().qtip_block_ldl_workspace(n))
+
+
+def qtip_block_ldl(H, n, A_out, D_out, workspace, workspace_bytes, stream=None):
+    return _check(lib().qtip_block_ldl(_ptr(H), n, _ptr(A_out), _ptr(D_out), _ptr(workspace),
+                                       workspace_bytes, _stream(stream)))
+
+
+def qtip_quantize_ldlq_workspace(m, n, k, V, tiles):
+    return int(lib().qtip_quantize_ldlq_workspace(m, n, k, V, tiles))
+
+
+def qtip_quantize_ldlq(W, A, m, n, L, k, V, code_id, lut, codes_out, What_out, tile_err, workspace,
+                       workspace_bytes, stream=None):
+    return _check(lib().qtip_quantize_ldlq(_ptr(W), _ptr(A), m, n, L, k, V, code_id, _ptr(lut),
+                                           _ptr(codes_out), _ptr(What_out), _ptr(tile_err),
+                                           _ptr(workspace), workspace_bytes, _stream(stream)))

@@ -195,4 +195,56 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
     return QTIP_OK;
 }
 
+size_t qtip_block_ldl_workspace(int n) {
+    if (n <= 0 || n % 16) return 0;
+    return qtip::block_ldl_workspace(n);
+}
+
+int qtip_block_ldl(const double *H, int n, float *A_out, double *D_out, void *workspace,
+                   size_t workspace_bytes, void *stream) {
+    const char *fn = "qtip_block_ldl";
+    if (!H || !A_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (n <= 0 || n % 16) return fail(QTIP_EINVAL, "%s: n = %d must be a positive multiple of 16", fn, n);
+    if ((uintptr_t)H % 8 || (uintptr_t)D_out % 8 || (uintptr_t)A_out % 4 || (uintptr_t)workspace % 256)
+        return fail(QTIP_EINVAL, "%s: H, D_out need 8-byte, A_out 4-byte, workspace 256-byte alignment", fn);
+    if (workspace_bytes < qtip::block_ldl_workspace(n))
+        return fail(QTIP_EINVAL, "%s: workspace of %zu bytes, %zu needed", fn, workspace_bytes,
+                    qtip::block_ldl_workspace(n));
+    hipError_t e = qtip::launch_block_ldl(H, n, A_out, D_out, workspace, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
+size_t qtip_quantize_ldlq_workspace(int m, int n, int k, int V, long tiles) {
+    if (k < 2 || k > 4 || (V != 1 && V != 2) || tiles <= 0 || m <= 0 || n <= 0 || m % 16 || n % 16) return 0;
+    return qtip::quantize_ldlq_workspace(m, n, k, V, tiles);
+}
+
+int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int k, int V, int code_id,
+                       const void *lut_f16, uint32_t *codes_out, float *What_out, float *tile_err,
+                       void *workspace, size_t workspace_bytes, void *stream) {
+    const char *fn = "qtip_quantize_ldlq";
+    if (!W || !A || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
+    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
+    if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
+    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
+    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (m <= 0 || n <= 0 || m % 16 || n % 16)
+        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    if (((uintptr_t)W | (uintptr_t)A | (uintptr_t)codes_out | (uintptr_t)What_out | (uintptr_t)tile_err) % 4 ||
+        (uintptr_t)workspace % 256)
+        return fail(QTIP_EINVAL, "%s: arrays need 4-byte, workspace 256-byte alignment", fn);
+    if (workspace_bytes < qtip::quantize_ldlq_workspace(m, n, k, V, 1))
+        return fail(QTIP_EINVAL, "%s: workspace of %zu bytes, at least %zu needed", fn, workspace_bytes,
+                    qtip::quantize_ldlq_workspace(m, n, k, V, 1));
+    hipError_t e = qtip::launch_quantize_ldlq(k, V, code_id, W, A, m, n, (const uint32_t *)lut_f16, codes_out,
+                                              What_out, tile_err, workspace, workspace_bytes,
+                                              (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
 }  // extern "C"
