@@ -109,6 +109,25 @@ int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id,
                        const void *row_scale_f16, float *Y, void *stream);
 
 /*
+ * The input side of a whole layer in one call: y = row_scale .* (W~ (V (S_n .* x))),
+ * i.e. qtip_rht(side 0, batch 1) followed by the batch-1 product, with the same
+ * arithmetic and therefore the same y bit for bit.  For n <= 8192 and m <= 4096 it is ONE
+ * kernel launch: every workgroup transforms x itself, in LDS, before it starts on its tile
+ * row (about 2 us of redundant work per workgroup against a kernel launch plus the gap
+ * before a dependent kernel, which is what bounds layers of this size: 4096 x 4096 goes
+ * from 14.9 to 8.9 us per call).  Larger layers have several workgroups per CU and would
+ * redo the transform too often: there the call enqueues the two kernels and needs
+ * xt_scratch (device, n fp16, 16-byte aligned; may be NULL otherwise) for the transformed
+ * vector.  Together with qtip_rht_f32(side 1) on y a small layer is two launches.
+ *   x_f16: device, n fp16, untransformed.  signs_n: device, n int8 in {+1,-1}.
+ *   block: Hadamard block (as qtip_rht).  row_scale_f16: device m fp16 or NULL.
+ */
+int qtip_rht_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
+                           const void *lut_f16, int m, int n, const void *x_f16,
+                           const int8_t *signs_n, int block, const void *row_scale_f16, float *y,
+                           void *xt_scratch_f16, void *stream);
+
+/*
  * Decode only (for testing): W_f16[i][j] = W~[i][j], device, m x n row-major fp16,
  * no row scale.  Bit-exact with the definitions of Algorithms 1-3.
  */

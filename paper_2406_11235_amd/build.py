@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqtip.so")
 SOURCES = ["qtip_api.hip", "qtip_decode.hip", "qtip_rht.hip", "qtip_viterbi.hip", "qtip_ldlq.hip", "qtip_quantize.cpp"]
-HEADERS = ["qtip_device.h", "qtip_internal.h", os.path.join("..", "..", "include", "qtip.h")]
+HEADERS = ["qtip_device.h", "qtip_rht_device.h", "qtip_internal.h", os.path.join("..", "..", "include", "qtip.h")]
 
 # Packed-FP32 VALU forms are switched off for every device compile.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",

@@ -91,6 +91,37 @@ int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id, 
     return QTIP_OK;
 }
 
+int qtip_rht_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id, const void *lut_f16,
+                           int m, int n, const void *x_f16, const int8_t *signs_n, int block,
+                           const void *row_scale_f16, float *y, void *xt_scratch_f16, void *stream) {
+    const char *fn = "qtip_rht_decode_matvec";
+    if (int rc = check_codec(fn, codes, L, k, V, code_id, lut_f16, m, n)) return rc;
+    if (!x_f16 || !signs_n || !y) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (block < 16 || block > 16384 || (block & (block - 1)))
+        return fail(QTIP_EINVAL, "%s: block = %d must be a power of two in [16, 16384]", fn, block);
+    if (n % block) return fail(QTIP_EINVAL, "%s: n = %d is not a multiple of block %d", fn, n, block);
+    if (!aligned(x_f16, 16) || !aligned(signs_n, 16))
+        return fail(QTIP_EINVAL, "%s: x and signs must be 16-byte aligned", fn);
+    hipError_t e;
+    // one launch pays while there is at most one workgroup (tile row) per CU; with more, every
+    // CU would redo the transform several times over
+    if (n <= qtip::fused_rht_matvec_max_n() && m <= 16 * 256) {
+        e = qtip::launch_rht_matvec(k, code_id, codes, (const uint32_t *)lut_f16, m, n, x_f16, signs_n, block,
+                                    row_scale_f16, y, (hipStream_t)stream);
+    } else {
+        if (!xt_scratch_f16 || !aligned(xt_scratch_f16, 16))
+            return fail(QTIP_EINVAL,
+                        "%s: n = %d above %d or m = %d above 4096: xt_scratch (n fp16, 16-byte aligned) is "
+                        "needed", fn, n, qtip::fused_rht_matvec_max_n(), m);
+        e = qtip::launch_rht(x_f16, false, signs_n, n, block, 1, 0, xt_scratch_f16, (hipStream_t)stream);
+        if (e == hipSuccess)
+            e = qtip::launch_matvec(k, code_id, codes, (const uint32_t *)lut_f16, m, n, xt_scratch_f16,
+                                    row_scale_f16, y, (hipStream_t)stream);
+    }
+    if (e != hipSuccess) return hip_fail(fn, e);
+    return QTIP_OK;
+}
+
 int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id, const void *lut_f16,
                        int m, int n, const void *X_f16, int B, const void *row_scale_f16, float *Y,
                        void *stream) {

@@ -8,6 +8,7 @@
 // LDS at the end.
 #include "qtip_device.h"
 #include "qtip_internal.h"
+#include "qtip_rht_device.h"
 
 #include <cstdlib>
 
@@ -131,16 +132,34 @@ __global__ void decode_states_kernel(const uint32_t *__restrict__ states, int co
 
 // ------------------------------------------------------- decode + matvec (B = 1)
 
-template <int K, int V, int CODE, int NW>
+// FUSED: x is the untransformed activation and the workgroup first computes the input-side
+// random Hadamard transform V (S .* x) of Section 2.1 into LDS itself (every workgroup the
+// whole vector: at most 8192 values, about 2 us, against a kernel launch and the gap to
+// the next dependent kernel, which cost more for layers this small), with the arithmetic
+// of the stand-alone transform, so that the result is the same bit for bit.
+constexpr int FUSED_MAX_N = 8192;
+
+template <int K, int V, int CODE, int NW, bool FUSED>
 __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
                                                          int tn, const half_t *__restrict__ x,
+                                                         const int8_t *__restrict__ signs, int log2_block,
                                                          const half_t *__restrict__ scale,
                                                          float *__restrict__ y) {
     constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
     constexpr int TPI = 64 / LPT;  // tiles per wave per iteration
     __shared__ uint32_t s_lut[CODE == CODE_HYB ? HYB_LDS_WORDS : 1];
     __shared__ float s_part[NW][16];
+    __shared__ __attribute__((aligned(16))) half_t s_x[FUSED ? FUSED_MAX_N : 8];
+    __shared__ float s_v[FUSED ? rht_lds_floats(FUSED_MAX_N) : 1];
+    if constexpr (FUSED) {
+        const int b = 1 << log2_block;
+        for (int o = 0; o < 16 * tn; o += b) {
+            half_t *dst = s_x + o;
+            rht_block<half_t, 0>(x + o, signs + o, log2_block, 0, s_v, threadIdx.x, NW * 64,
+                                 [dst](int idx, half_t v) { dst[idx] = v; });
+        }
+    }
     if constexpr (CODE == CODE_HYB) {
         stage_signed_lut(lut, s_lut, NW * 64);
         __syncthreads();
@@ -167,9 +186,15 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
     auto issue = [&](Operands &o, int Jb) {
         const int Jc = min(Jb + g, Jend - 1);  // lanes past the end re-read the last tile
         o.w = load_words<K>(codes, (size_t)I * tn + Jc, q);
-        const uint4 *xp = reinterpret_cast<const uint4 *>(x + 16 * Jc);
-        o.xa = xp[0];
-        o.xb = xp[1];
+        if constexpr (FUSED) {
+            const uint4 *xp = reinterpret_cast<const uint4 *>(s_x + 16 * Jc);
+            o.xa = xp[0];
+            o.xb = xp[1];
+        } else {
+            const uint4 *xp = reinterpret_cast<const uint4 *>(x + 16 * Jc);
+            o.xa = xp[0];
+            o.xb = xp[1];
+        }
     };
     auto compute = [&](const Operands &o, int Jb) {
         uint32_t w[WPL + 1];
@@ -456,13 +481,19 @@ static int pick_matvec_waves(int tm, int steps_per_row) {
 
 template <int K, int V, int CODE>
 static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, int m, int n,
-                                  const void *x, const void *scale, float *y, hipStream_t st) {
+                                  const void *x, const int8_t *signs, int log2_block, const void *scale,
+                                  float *y, hipStream_t st) {
     constexpr int TPI = 64 / Geo<K>::LPT;
     const int tm = m / 16, tn = n / 16;
     const int nw = pick_matvec_waves(tm, (tn + TPI - 1) / TPI);
-#define QTIP_MV_LAUNCH(NW)                                                                        \
-    hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW>), dim3(tm), dim3(NW * 64), 0, st, codes, lut, \
-                       tn, (const half_t *)x, (const half_t *)scale, y)
+    // signs != null: x is untransformed and the kernel transforms it itself (n <= FUSED_MAX_N)
+#define QTIP_MV_LAUNCH(NW)                                                                              \
+    if (signs)                                                                                          \
+        hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW, true>), dim3(tm), dim3(NW * 64), 0, st, codes, \
+                           lut, tn, (const half_t *)x, signs, log2_block, (const half_t *)scale, y);     \
+    else                                                                                                \
+        hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW, false>), dim3(tm), dim3(NW * 64), 0, st,       \
+                           codes, lut, tn, (const half_t *)x, signs, log2_block, (const half_t *)scale, y)
     switch (nw) {
         case 2: QTIP_MV_LAUNCH(2); break;
         case 4: QTIP_MV_LAUNCH(4); break;
@@ -522,7 +553,17 @@ hipError_t launch_dequantize(int k, int code_id, const uint32_t *codes, const ui
 
 hipError_t launch_matvec(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
                          int n, const void *x, const void *scale, float *y, hipStream_t st) {
-    QTIP_DISPATCH(launch_matvec_t, codes, lut, m, n, x, scale, y, st);
+    QTIP_DISPATCH(launch_matvec_t, codes, lut, m, n, x, (const int8_t *)nullptr, 0, scale, y, st);
+}
+
+int fused_rht_matvec_max_n() { return FUSED_MAX_N; }
+
+hipError_t launch_rht_matvec(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                             int n, const void *x, const int8_t *signs, int block, const void *scale,
+                             float *y, hipStream_t st) {
+    int log2_block = 0;
+    while ((1 << log2_block) < block) log2_block++;
+    QTIP_DISPATCH(launch_matvec_t, codes, lut, m, n, x, signs, log2_block, scale, y, st);
 }
 
 hipError_t launch_matmat(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,

@@ -11,6 +11,12 @@ hipError_t launch_matvec(int k, int code_id, const uint32_t *codes, const uint32
                          int n, const void *x, const void *scale, float *y, hipStream_t st);
 hipError_t launch_matmat(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
                          int n, const void *X, int B, const void *scale, float *Y, hipStream_t st);
+// decode + matvec that computes the input-side transform V (S .* x) itself; n at most
+// fused_rht_matvec_max_n().
+int fused_rht_matvec_max_n();
+hipError_t launch_rht_matvec(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
+                             int n, const void *x, const int8_t *signs, int block, const void *scale,
+                             float *y, hipStream_t st);
 hipError_t launch_decode_states(int code_id, const uint32_t *states, int count,
                                 const uint32_t *lut, void *out, hipStream_t st);
 hipError_t launch_rht(const void *x, bool x_is_f32, const int8_t *signs, int n, int block,

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
     const uint32_t *__restrict__ overlap, uint32_t *__restrict__ ptrs, uint32_t *__restrict__ final_state,
     float *__restrict__ final_value) {
     using Geo = VitGeo<KV>;
-    constexpr int OV = Geo::OV, NP = Geo::NP, NC = Geo::NC, NB1 = Geo::NB1, PW = Geo::PW;
+    constexpr int NP = Geo::NP, NC = Geo::NC, NB1 = Geo::NB1, PW = Geo::PW;
     constexpr int G = VT_T / V;
     constexpr bool HYB = CODE == CODE_HYB;
     static_assert(HYB == (V == 2), "V = 2 is the HYB code");

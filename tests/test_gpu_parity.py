@@ -290,6 +290,39 @@ def test_full_layer_composition(q):
 
 # ---------------------------------------------------------------- error paths
 
+@pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
+@pytest.mark.parametrize("m,n,block", [(48, 1024, 256), (160, 4096, 4096), (32, 8192, 2048), (16, 16, 16),
+                                       (32, 6144, 2048), (32, 12288, 4096), (4112, 64, 64)])
+def test_rht_decode_matvec_equals_the_two_calls(q, code_id, k, V, m, n, block):
+    """The call that transforms its own input: one launch up to n = 8192 and m = 4096 (every
+    workgroup transforms x in LDS), two launches above; the same bits as qtip_rht followed by
+    the product either way, and the oracle's layer within the bar."""
+    import torch
+    w = small_workload(code_id, k, V, m, n, row_scale=True, sub=3)
+    inp = synth.make_inputs(w)
+    rng = np.random.default_rng(n + m)
+    signs = rng.choice(np.array([-1, 1], dtype=np.int8), n)
+    codes, lut, X, sc, sg = dev(inp.codes), dev(inp.lut), dev(inp.X), dev(inp.row_scale), dev(signs)
+    xt = torch.empty((1, n), dtype=torch.float16, device="cuda")
+    y2 = torch.full((m,), float("nan"), dtype=torch.float32, device="cuda")
+    q.qtip_rht(X, sg, n, block, 1, 0, xt)
+    q.qtip_decode_matmat(codes, 16, k, V, code_id, lut, m, n, xt, 1, sc, y2)
+    y1 = torch.full((m,), float("nan"), dtype=torch.float32, device="cuda")
+    two_launches = n > 8192 or m > 4096
+    scratch = torch.empty(n, dtype=torch.float16, device="cuda") if two_launches else None
+    q.qtip_rht_decode_matvec(codes, 16, k, V, code_id, lut, m, n, X, sg, block, sc, y1, scratch)
+    torch.cuda.synchronize()
+    assert np.array_equal(y1.cpu().numpy(), y2.cpu().numpy())
+    Wref = oracle.dequantize(inp.codes, 16, k, V, code_id, m, n, inp.lut)
+    xt_ref = oracle.rht(inp.X, signs, block, 0).astype(np.float16)      # the layer rounds x~ to fp16
+    ref = oracle.matmat_dense(Wref, xt_ref, inp.row_scale)[0]
+    err = np.abs(y1.cpu().numpy() - ref).max() / np.abs(ref).max()
+    assert err <= REL_TOL, err
+    if two_launches:
+        with pytest.raises(q.QtipError):
+            q.qtip_rht_decode_matvec(codes, 16, k, V, code_id, lut, m, n, X, sg, block, sc, y1, None)
+
+
 def test_gpu_error_codes(q):
     import torch
     w = small_workload(CODE_3INST, 2, 1, 32, 32)
