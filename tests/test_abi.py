@@ -76,6 +76,12 @@ def test_argument_errors_need_no_gpu(q):
         (L.qtip_rht(p, p, 64, 64, 1, 2, p, None), EINVAL),
         (L.qtip_rht(p, p, 8, 8, 1, 0, p, None), EINVAL),
         (L.qtip_rht_f32(p, p, 64, 64, 1, 0, p, None), EINVAL),     # aliasing refused
+        (L.qtip_rht_decode_matvec(p, 16, 2, 1, 1, None, 16, 64, None, p, 64, None, p, None, None), EINVAL),
+        (L.qtip_rht_decode_matvec(p, 16, 2, 1, 1, None, 16, 64, p, p, 48, None, p, None, None), EINVAL),
+        (L.qtip_rht_decode_matvec(p, 16, 2, 1, 1, None, 16, 96, p, p, 64, None, p, None, None), EINVAL),
+        (L.qtip_rht_decode_matvec(p, 16, 2, 1, 1, None, 16, 16384, p, p, 64, None, p, None, None), EINVAL),
+        (L.qtip_rht_decode_matvec(p, 16, 2, 1, 1, None, 8192, 64, p, p, 64, None, p, None, None), EINVAL),
+        (L.qtip_rht_decode_matvec(p, 16, 7, 1, 1, None, 16, 64, p, p, 64, None, p, None, None), EUNSUP),
         (L.qtip_quantize(None, 16, 16, 16, 2, 1, 1, None, p, None), EINVAL),
         (L.qtip_quantize(p, 16, 16, 16, 2, 2, 2, None, p, None), EINVAL),
         (L.qtip_quantize(p, 16, 16, 16, 6, 1, 1, None, p, None), EUNSUP),
