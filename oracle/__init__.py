@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qtip_oracle.c")
 _LIB = os.path.join(_HERE, "libqtip_oracle.so")
 
-CODE_1MAD, CODE_3INST, CODE_HYB = 0, 1, 2
+CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2 = 0, 1, 2, 3
 
 
 def build(force=False):
@@ -56,6 +56,8 @@ def lib():
         L.orc_code_3inst.argtypes = [c.c_uint32]
         L.orc_code_hyb.restype = None
         L.orc_code_hyb.argtypes = [c.c_uint32, i32, vp, vp]
+        L.orc_code_hyb2.restype = None
+        L.orc_code_hyb2.argtypes = [c.c_uint32, i32, vp, vp]
         L.orc_codebook.restype = i32
         L.orc_codebook.argtypes = [i32, i32, i32, vp, i32, vp]
         L.orc_decode_sequence.restype = None
@@ -159,6 +161,14 @@ def code_hyb(x, lut, Q=9):
     assert lut.size == 2 << Q
     out = np.zeros(2, dtype=np.uint16)
     lib().orc_code_hyb(int(x), Q, _p(lut), _p(out))
+    return int(out[0]), int(out[1])
+
+
+def code_hyb2(x, lut, Q=9):
+    lut = _u16(lut).reshape(-1)
+    assert lut.size == 2 << Q
+    out = np.zeros(2, dtype=np.uint16)
+    lib().orc_code_hyb2(int(x), Q, _p(lut), _p(out))
     return int(out[0]), int(out[1])
 
 

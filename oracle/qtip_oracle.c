@@ -12,7 +12,8 @@
  *   - the packed bitstream and the L-bit state window of the bitshift
  *     trellis (Section 3.1; Figure 1; tail-biting wrap, Section 3.2);
  *   - the state -> value codes 1MAD (Algorithm 1), 3INST (Algorithm 2) and
- *     HYB (Algorithm 3), plus a plain table code C[2^L][V] (Section 2.3);
+ *     HYB (Algorithm 3) and its two-sign-flip form, plus a plain table code
+ *     C[2^L][V] (Section 2.3);
  *   - decode of a 16x16 tile and of a whole matrix (Section 4: a T_x x T_y
  *     block is one sequence; Algorithm 5's reshape gives the order);
  *   - dense fp64 matrix-vector / matrix-matrix product with the decoded
@@ -50,6 +51,7 @@
 #define ORC_CODE_1MAD 0
 #define ORC_CODE_3INST 1
 #define ORC_CODE_HYB 2
+#define ORC_CODE_HYB2 3
 
 int orc_threads(void) {
 #ifdef _OPENMP
@@ -168,6 +170,22 @@ void orc_code_hyb(uint32_t x, int Q, const uint16_t *lut, uint16_t out[2]) {
     if ((X >> 15) & 1u) out[1] ^= 0x8000u;
 }
 
+/*
+ * The two-sign-flip form of Algorithm 3 (Section 3.1.2 notes it as a free
+ * extension that the paper's numbers do not use): bit 31 of the hash is XORed
+ * alongside bit 15, so each of the two looked-up entries gets a sign of its
+ * own and a state selects one of 2^(Q+2) vectors.  Reading: bit 15 keeps the
+ * second entry, as in orc_code_hyb; bit 31 takes the first.
+ */
+void orc_code_hyb2(uint32_t x, int Q, const uint16_t *lut, uint16_t out[2]) {
+    uint32_t X = x * x + x;
+    uint32_t idx = (X >> (15 - Q)) & ((1u << Q) - 1u);
+    out[0] = lut[2 * idx + 0];
+    out[1] = lut[2 * idx + 1];
+    if ((X >> 31) & 1u) out[0] ^= 0x8000u;
+    if ((X >> 15) & 1u) out[1] ^= 0x8000u;
+}
+
 /* One state -> V fp16 values for the given code. */
 static void orc_code_eval(int code_id, uint32_t state, const uint16_t *lut, int Q,
                           uint16_t *out) {
@@ -175,13 +193,15 @@ static void orc_code_eval(int code_id, uint32_t state, const uint16_t *lut, int 
         out[0] = orc_code_1mad(state);
     else if (code_id == ORC_CODE_3INST)
         out[0] = orc_code_3inst(state);
+    else if (code_id == ORC_CODE_HYB2)
+        orc_code_hyb2(state, Q, lut, out);
     else
         orc_code_hyb(state, Q, lut, out);
 }
 
 /* Full codebook C[2^L][V] as doubles (used by the quantizer functions). */
 int orc_codebook(int L, int V, int code_id, const uint16_t *lut, int Q, double *C) {
-    if (code_id == ORC_CODE_HYB ? V != 2 : V != 1) return -1;
+    if ((code_id == ORC_CODE_HYB || code_id == ORC_CODE_HYB2) ? V != 2 : V != 1) return -1;
     for (uint32_t x = 0; x < (1u << L); x++) {
         uint16_t v[2];
         orc_code_eval(code_id, x, lut, Q, v);

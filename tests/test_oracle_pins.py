@@ -609,3 +609,36 @@ def test_ldlq_without_correlation_is_plain_quantization_and_feedback_helps():
     codes1, What1, _ = oracle.ldlq_quantize_f32(W, (Lm - np.eye(n)).astype(np.float32), 16, 2, 1, CODE_3INST)
     loss = lambda Wh: np.trace((Wh - W).astype(np.float64) @ H @ (Wh - W).astype(np.float64).T)
     assert loss(What1) < 0.8 * loss(What0)               # Section 2.1: feedback lowers the proxy loss
+
+
+# ----------------------------------------------- HYB with two sign flips
+
+def test_hyb2_is_hyb_with_an_independent_sign_on_the_first_entry():
+    """Section 3.1.2's free extension of Algorithm 3: same row, bit 15 of the hash on the second
+    entry as before, bit 31 on the first; 2^(Q+2) = 2048 signed vectors, all of them reached."""
+    from oracle import CODE_HYB2
+    rng = np.random.default_rng(17)
+    lut = (np.abs(rng.standard_normal((512, 2))) + 0.01).astype(np.float16)     # signs come from the hash only
+    lw = lut.view(np.uint16)
+    x = np.arange(1 << 16, dtype=np.uint64)
+    X = (x * x + x) & 0xFFFFFFFF
+    idx = ((X >> 6) & 511).astype(np.int64)
+    s0 = ((X >> 31) & 1).astype(np.uint16)
+    s1 = ((X >> 15) & 1).astype(np.uint16)
+    want = np.stack([lw[idx, 0] ^ (s0 << 15), lw[idx, 1] ^ (s1 << 15)], axis=1)
+    C2 = oracle.codebook(16, 2, CODE_HYB2, lut).astype(np.float16).view(np.uint16)
+    assert np.array_equal(C2, want)
+    C1 = oracle.codebook(16, 2, CODE_HYB, lut).astype(np.float16).view(np.uint16)
+    assert np.array_equal(C2[:, 1], C1[:, 1])                       # second entry: unchanged
+    assert np.array_equal(C2[:, 0] & 0x7FFF, C1[:, 0] & 0x7FFF)     # first entry: same magnitude
+    # closed form at L = 16: x*x + x never wraps, so bit 31 is set exactly when x >= 46341
+    # (46340 * 46341 < 2^31 <= 46341 * 46342): the extra sign follows the top bits of the state
+    assert np.array_equal(s0, (x >= 46341).astype(np.uint16))
+    assert len({(int(i), int(a), int(b)) for i, a, b in zip(idx, s0, s1)}) == 2048
+    for xx in (0, 1, 255, 40000, 65535):
+        assert oracle.code_hyb2(xx, lut) == (int(want[xx, 0]), int(want[xx, 1]))
+    # and it decodes through the common paths
+    codes = rng.integers(0, 1 << 32, (2, 16), dtype=np.uint64).astype(np.uint32)
+    W = oracle.dequantize(codes, 16, 2, 2, CODE_HYB2, 16, 32, lut)
+    st = [oracle.state(codes[1], 512, 16, 4, t) for t in range(128)]
+    assert np.array_equal(W[:, 16:].reshape(-1), want[st].reshape(-1))
