@@ -30,7 +30,7 @@
  *
  * SUPPORTED PARAMETERS
  *   L = 16 only.  code_id QTIP_CODE_1MAD / QTIP_CODE_3INST with V = 1 and
- *   k in {2, 3, 4}; QTIP_CODE_HYB (Q = 9) with V = 2 and k in {2, 3, 4}.
+ *   k in {2, 3, 4}; QTIP_CODE_HYB and QTIP_CODE_HYB2 (Q = 9) with V = 2 and k in {2, 3, 4}.
  *   m and n multiples of 16.  Anything else returns QTIP_EUNSUPPORTED / QTIP_EINVAL.
  *
  * OWNERSHIP, STREAMS, ERRORS
@@ -63,6 +63,9 @@ extern "C" {
 #define QTIP_CODE_1MAD 0  /* Algorithm 1 */
 #define QTIP_CODE_3INST 1 /* Algorithm 2 */
 #define QTIP_CODE_HYB 2   /* Algorithm 3, Q = 9, one sign flip */
+#define QTIP_CODE_HYB2 3  /* the same with bit 31 of the hash also XORed (Section 3.1.2): the first
+                             entry gets a sign of its own; for L = 16 that bit is set exactly when
+                             the state is at least 46341 */
 
 /*
  * Random Hadamard transform of activations (Section 2.1: W~ = V_m S_m W S_n V_n^T,

@@ -9,6 +9,8 @@
 
 namespace {
 
+bool is_hyb(int code_id) { return code_id == QTIP_CODE_HYB || code_id == QTIP_CODE_HYB2; }
+
 thread_local char g_err[512] = "";
 
 int fail(int code, const char *fmt, ...) {
@@ -29,14 +31,15 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 int check_codec(const char *fn, const void *codes, int L, int k, int V, int code_id,
                 const void *lut, int m, int n) {
     if (!codes) return fail(QTIP_EINVAL, "%s: codes is NULL", fn);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
+        code_id != QTIP_CODE_HYB2)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
     if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
     if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
-    const int wantV = code_id == QTIP_CODE_HYB ? 2 : 1;
+    const int wantV = is_hyb(code_id) ? 2 : 1;
     if (V != wantV)
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d (code %d needs V = %d)", fn, V, code_id, wantV);
-    if (code_id == QTIP_CODE_HYB && !lut) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (is_hyb(code_id) && !lut) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
     if (m <= 0 || n <= 0 || m % 16 || n % 16)
         return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
     if (!aligned(codes, 16)) return fail(QTIP_EINVAL, "%s: codes must be 16-byte aligned", fn);
@@ -158,12 +161,13 @@ int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code
     const char *fn = "qtip_decode_states";
     if (!states || !out_f16) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (count < 0) return fail(QTIP_EINVAL, "%s: count = %d", fn, count);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
+        code_id != QTIP_CODE_HYB2)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
     if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
-    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+    if (V != (is_hyb(code_id) ? 2 : 1))
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
     if (count == 0) return QTIP_OK;
     hipError_t e = qtip::launch_decode_states(code_id, states, count, (const uint32_t *)lut_f16,
                                               out_f16, (hipStream_t)stream);
@@ -175,13 +179,14 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
                   const void *lut_f16, uint32_t *codes_out, double *mse_out) {
     const char *fn = "qtip_quantize";
     if (!W || !codes_out) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
+        code_id != QTIP_CODE_HYB2)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
     if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
     if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
-    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+    if (V != (is_hyb(code_id) ? 2 : 1))
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
     if (m <= 0 || n <= 0 || m % 16 || n % 16)
         return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
     int rc;
@@ -206,13 +211,14 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
                       size_t workspace_bytes, void *stream) {
     const char *fn = "qtip_quantize_gpu";
     if (!W || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
+        code_id != QTIP_CODE_HYB2)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
     if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
     if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
-    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+    if (V != (is_hyb(code_id) ? 2 : 1))
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
     if (m <= 0 || n <= 0 || m % 16 || n % 16)
         return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
     if (((uintptr_t)W | (uintptr_t)codes_out | (uintptr_t)tile_err) % 4 || (uintptr_t)workspace % 256)
@@ -256,13 +262,14 @@ int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int 
                        void *workspace, size_t workspace_bytes, void *stream) {
     const char *fn = "qtip_quantize_ldlq";
     if (!W || !A || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB)
+    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
+        code_id != QTIP_CODE_HYB2)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
     if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
     if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
-    if (V != (code_id == QTIP_CODE_HYB ? 2 : 1))
+    if (V != (is_hyb(code_id) ? 2 : 1))
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (code_id == QTIP_CODE_HYB && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
     if (m <= 0 || n <= 0 || m % 16 || n % 16)
         return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
     if (((uintptr_t)W | (uintptr_t)A | (uintptr_t)codes_out | (uintptr_t)What_out | (uintptr_t)tile_err) % 4 ||

@@ -56,7 +56,7 @@ __device__ __forceinline__ void decode_row(const uint32_t (&w)[NWD], int rr,
     for (int c = 0; c < 8; c++) {
         if constexpr (V == 2) {
             uint32_t st = window16(w, rr * 16 * K + c * 2 * K);
-            out[c] = code_hyb(st, lut);
+            out[c] = CODE == CODE_HYB2 ? code_hyb2(st, lut) : code_hyb(st, lut);
         } else {
             uint32_t s0 = window16(w, rr * 16 * K + (2 * c) * K);
             uint32_t s1 = window16(w, rr * 16 * K + (2 * c + 1) * K);
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t *__restr
     constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
     constexpr int TPW = 64 / LPT;  // tiles per wave per step
     __shared__ uint32_t s_lut[1 << HYB_Q];
-    if constexpr (CODE == CODE_HYB) stage_lut(lut, s_lut);
+    if constexpr (code_is_hyb(CODE)) stage_lut(lut, s_lut);
     const int lane = threadIdx.x & 63;
     const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const long tile = wave * TPW + lane / LPT;
@@ -119,8 +119,8 @@ __global__ void decode_states_kernel(const uint32_t *__restrict__ states, int co
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
     uint32_t st = states[i] & 0xFFFFu;
-    if constexpr (CODE == CODE_HYB) {
-        half2_t h = code_hyb(st, lut);
+    if constexpr (code_is_hyb(CODE)) {
+        half2_t h = CODE == CODE_HYB2 ? code_hyb2(st, lut) : code_hyb(st, lut);
         out[2 * i] = h.x;
         out[2 * i + 1] = h.y;
     } else if constexpr (CODE == CODE_3INST) {
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
                                                          float *__restrict__ y) {
     constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
     constexpr int TPI = 64 / LPT;  // tiles per wave per iteration
-    __shared__ uint32_t s_lut[CODE == CODE_HYB ? HYB_LDS_WORDS : 1];
+    __shared__ uint32_t s_lut[code_is_hyb(CODE) ? HYB_LDS_WORDS : 1];
     __shared__ float s_part[NW][16];
     __shared__ __attribute__((aligned(16))) half_t s_x[FUSED ? FUSED_MAX_N : 8];
     __shared__ float s_v[FUSED ? rht_lds_floats(FUSED_MAX_N) : 1];
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
                                  [dst](int idx, half_t v) { dst[idx] = v; });
         }
     }
-    if constexpr (CODE == CODE_HYB) {
+    if constexpr (code_is_hyb(CODE)) {
         stage_signed_lut(lut, s_lut, NW * 64);
         __syncthreads();
     }
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
                                                          float *__restrict__ Y) {
     constexpr int R = 2;
     constexpr int NWORDS = 8 * K;
-    __shared__ uint32_t s_lut[CODE == CODE_HYB ? HYB_LDS_WORDS : 1];
+    __shared__ uint32_t s_lut[code_is_hyb(CODE) ? HYB_LDS_WORDS : 1];
     // one buffer, used twice: in the loop each wave's staging region (SR batch rows at a
     // time, 128 bytes each, padded to 144 so that the row-wise writes and the
     // column-wise reads both spread over the banks), after it the partial sums
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
     constexpr int STAGE_FLOATS = STAGE ? NW * SR * XST / 4 : 0;
     __shared__ __attribute__((aligned(16))) float s_buf[PART_FLOATS > STAGE_FLOATS ? PART_FLOATS : STAGE_FLOATS];
     float(*s_part)[R][NB][4][64] = reinterpret_cast<float(*)[R][NB][4][64]>(s_buf);
-    if constexpr (CODE == CODE_HYB) {
+    if constexpr (code_is_hyb(CODE)) {
         stage_signed_lut(lut, s_lut, NW * 64);
         __syncthreads();
     }
@@ -531,7 +531,11 @@ static hipError_t launch_matmat_t(const uint32_t *codes, const uint32_t *lut, in
 
 #define QTIP_DISPATCH(FN, ...)                                                         \
     do {                                                                               \
-        if (code_id == CODE_HYB) {                                                     \
+        if (code_id == CODE_HYB2) {                                                    \
+            if (k == 2) return FN<2, 2, CODE_HYB2>(__VA_ARGS__);                       \
+            if (k == 3) return FN<3, 2, CODE_HYB2>(__VA_ARGS__);                       \
+            return FN<4, 2, CODE_HYB2>(__VA_ARGS__);                                   \
+        } else if (code_id == CODE_HYB) {                                              \
             if (k == 2) return FN<2, 2, CODE_HYB>(__VA_ARGS__);                        \
             if (k == 3) return FN<3, 2, CODE_HYB>(__VA_ARGS__);                        \
             return FN<4, 2, CODE_HYB>(__VA_ARGS__);                                    \
@@ -575,7 +579,10 @@ hipError_t launch_matmat(int k, int code_id, const uint32_t *codes, const uint32
 hipError_t launch_decode_states(int code_id, const uint32_t *states, int count,
                                 const uint32_t *lut, void *out, hipStream_t st) {
     const int blocks = (count + 255) / 256;
-    if (code_id == CODE_HYB)
+    if (code_id == CODE_HYB2)
+        hipLaunchKernelGGL((decode_states_kernel<CODE_HYB2>), dim3(blocks), dim3(256), 0, st, states,
+                           count, lut, (half_t *)out);
+    else if (code_id == CODE_HYB)
         hipLaunchKernelGGL((decode_states_kernel<CODE_HYB>), dim3(blocks), dim3(256), 0, st, states,
                            count, lut, (half_t *)out);
     else if (code_id == CODE_3INST)

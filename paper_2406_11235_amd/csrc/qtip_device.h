@@ -31,6 +31,8 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 constexpr int CODE_1MAD = 0;
 constexpr int CODE_3INST = 1;
 constexpr int CODE_HYB = 2;
+constexpr int CODE_HYB2 = 3;  // HYB with a second sign flip (bit 31 of the hash on the first entry)
+__host__ __device__ constexpr bool code_is_hyb(int code) { return code == CODE_HYB || code == CODE_HYB2; }
 
 // Section 3.1.1 constants.
 constexpr uint32_t MAD_A = 34038481u, MAD_B = 76625530u;
@@ -98,6 +100,22 @@ __device__ __forceinline__ half2_t code_hyb(uint32_t x, const uint32_t *lut) {
     uint32_t X = x * x + x;
     uint32_t v = lut[(X >> (15 - HYB_Q)) & ((1u << HYB_Q) - 1u)];
     return as_half2(v ^ ((X & 0x8000u) << 16));
+}
+
+// The two-sign-flip form mentioned with Algorithm 3: bit 31 of the hash is XORed alongside
+// bit 15, which flips the first entry as well (an effective table of 2^(Q+2) vectors).
+__device__ __forceinline__ half2_t code_hyb2(uint32_t x, const uint32_t *lut) {
+    uint32_t X = x * x + x;
+    uint32_t v = lut[(X >> (15 - HYB_Q)) & ((1u << HYB_Q) - 1u)];
+    return as_half2(v ^ ((X & 0x8000u) << 16) ^ ((X >> 16) & 0x8000u));
+}
+// For 16-bit states x*x + x does not wrap, so its bit 31 is set exactly when x >= 46341.
+// Both halves of R are states: bit 15 of each half of the result is that comparison
+// (x >= 46341  <=>  bit 15 of x set and bit 15 of x - 46341 mod 2^16 clear).
+__device__ __forceinline__ uint32_t hyb2_sign_mask(uint32_t R) {
+    uint32_t D;
+    asm("v_pk_sub_u16 %0, %1, %2" : "=v"(D) : "v"(R), "v"(0xB505B505u));
+    return R & ~D & 0x80008000u;
 }
 
 // ------------------------------------------------------------- hot-loop pieces
@@ -239,6 +257,11 @@ template <int K, int CODE> struct RowDecode {
                         // state base+j in the high half of H, state base+j+G in the low half
                         h[base + j] = hyb_signed_lookup(lut, (H >> 20) & 0xFFCu);
                         h[base + j + G] = hyb_signed_lookup(lut, (H >> 4) & 0xFFCu);
+                        if constexpr (CODE == CODE_HYB2) {
+                            const uint32_t M = hyb2_sign_mask(R);
+                            h[base + j] ^= M >> 16;
+                            h[base + j + G] ^= M & 0x8000u;
+                        }
                     }
             } else {
 #pragma unroll
@@ -246,6 +269,7 @@ template <int K, int CODE> struct RowDecode {
                     const uint32_t st = window16(w, P0 + c * 2 * K);
                     const uint32_t X = st * st + st;
                     h[c] = hyb_signed_lookup(lut, (X >> 4) & 0xFFCu);
+                    if constexpr (CODE == CODE_HYB2) h[c] ^= (X >> 16) & 0x8000u;
                 }
             }
         }
@@ -331,7 +355,7 @@ template <int K> struct RowDot<K, CODE_1MAD> {
 // same way); the hot loop reads that 4 KiB table from LDS, built by the kernel from the
 // 512 stored rows: signed[s * 512 + idx] = row idx with entry 1 negated iff s.  One
 // shift and one mask turn a hash into a byte address, and no sign fix-up is left.
-template <int K> struct RowDot<K, CODE_HYB> {
+template <int K, bool TWO> struct RowDotHyb {
     const uint32_t *lut;  // LDS: the 1024 signed vectors
     __device__ __forceinline__ void init(const uint32_t *lds_lut) { lut = lds_lut; }
     __device__ __forceinline__ void prep_x(uint32_t (&)[8]) const {}
@@ -358,6 +382,11 @@ template <int K> struct RowDot<K, CODE_HYB> {
                         // hash bits 6..15 -> byte address; state base+j sits in the high half
                         v[rr][base + j] = hyb_signed_lookup(lut, (H >> 20) & 0xFFCu);
                         v[rr][base + j + G] = hyb_signed_lookup(lut, (H >> 4) & 0xFFCu);
+                        if constexpr (TWO) {  // TWO: the first entry's sign, from the states themselves
+                            const uint32_t M = hyb2_sign_mask(R);
+                            v[rr][base + j] ^= M >> 16;
+                            v[rr][base + j + G] ^= M & 0x8000u;
+                        }
                     }
             };
             issue_row(0);
@@ -377,11 +406,14 @@ template <int K> struct RowDot<K, CODE_HYB> {
                 for (int c = 0; c < 8; c++) {
                     const uint32_t st = window16(w, rr * 16 * K + c * 2 * K);
                     const uint32_t X = st * st + st;
-                    acc[rr] = __builtin_amdgcn_fdot2(as_half2(hyb_signed_lookup(lut, (X >> 4) & 0xFFCu)),
-                                                     as_half2(x[c]), acc[rr], false);
+                    uint32_t v = hyb_signed_lookup(lut, (X >> 4) & 0xFFCu);
+                    if constexpr (TWO) v ^= (X >> 16) & 0x8000u;
+                    acc[rr] = __builtin_amdgcn_fdot2(as_half2(v), as_half2(x[c]), acc[rr], false);
                 }
         }
     }
 };
+template <int K> struct RowDot<K, CODE_HYB> : RowDotHyb<K, false> {};
+template <int K> struct RowDot<K, CODE_HYB2> : RowDotHyb<K, true> {};
 
 }  // namespace qtip

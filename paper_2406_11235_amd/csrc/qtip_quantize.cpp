@@ -46,9 +46,11 @@ void build_codebook(int V, int code_id, const uint16_t *lut, std::vector<float> 
         } else {
             uint32_t X = x * x + x;
             uint32_t idx = (X >> 6) & 511u;
+            uint16_t v0 = lut[2 * idx];
             uint16_t v1 = lut[2 * idx + 1];
             if (X & 0x8000u) v1 ^= 0x8000u;
-            C[2 * (size_t)x] = half_bits_to_float(lut[2 * idx]);
+            if (code_id == 3 && (X >> 31)) v0 ^= 0x8000u;  // the two-sign-flip form
+            C[2 * (size_t)x] = half_bits_to_float(v0);
             C[2 * (size_t)x + 1] = half_bits_to_float(v1);
         }
     }

@@ -18,8 +18,8 @@
 //   phase 2: every thread reads the minimum of each of its states' prefixes back from
 //            LDS and adds the squared error of the state's code value.
 // Code values never change, so they sit in registers as packed fp16 (V = 1); for the
-// HYB code a state only selects one of 1024 signed table rows, so each step first
-// builds the 1024 squared errors in LDS and states carry a 10-bit row number.
+// HYB code a state only selects one of 1024 signed table rows (2048 with two sign flips), so
+// each step first builds their squared errors in LDS and states carry a row number.
 // A second, tiny kernel walks the back-pointers (one thread per sequence: the walk is a
 // chain of dependent loads, so it is run over a whole batch of sequences at once).
 // Algorithm 4 is forward / walk-to-the-middle / constrained forward / full walk.
@@ -105,12 +105,13 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
     using Geo = VitGeo<KV>;
     constexpr int NP = Geo::NP, NC = Geo::NC, NB1 = Geo::NB1, PW = Geo::PW;
     constexpr int G = VT_T / V;
-    constexpr bool HYB = CODE == CODE_HYB;
+    constexpr bool HYB = code_is_hyb(CODE);
+    constexpr int ROWS = CODE == CODE_HYB2 ? 2048 : 1024;  // signed table rows a state can select
     static_assert(HYB == (V == 2), "V = 2 is the HYB code");
     // LDS: minima (or, for kV = 8, per-thread partial minima, their predecessors and the
     // 256 minima), reused for the final reduction; then the HYB error table
     constexpr int BEST_FLOATS = Geo::LOCAL ? vit_max(NP, 2 * VT_NT) : 2 * VT_NT + NP;
-    __shared__ float s_mem[BEST_FLOATS + VT_T + (HYB ? 1024 : 0)];
+    __shared__ float s_mem[BEST_FLOATS + VT_T + (HYB ? ROWS : 0)];
     float *const s_best = s_mem;
     float *const s_seq = s_mem + BEST_FLOATS;      // the sequence
     float *const s_D = s_mem + BEST_FLOATS + VT_T;  // HYB only
@@ -136,7 +137,8 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
         const uint32_t y = (uint32_t)(r * VT_NT + tid);
         if constexpr (HYB) {
             const uint32_t X = y * y + y;
-            const uint32_t row = (X >> (15 - HYB_Q)) & 1023u;  // table index and sign bit
+            uint32_t row = (X >> (15 - HYB_Q)) & 1023u;  // table index and sign bit
+            if constexpr (CODE == CODE_HYB2) row |= (X >> 31) << 10;  // second sign bit
             if (r & 1)
                 ipk[r >> 1] |= row << 16;
             else
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
     // squared error of table row `row` against (s0, s1)
     auto hyb_error = [&](int row, float s0, float s1) -> float {
         const half2_t c = as_half2(lut[row & 511]);
-        const float c0 = (float)c.x;
+        const float c0 = (row & 1024) ? -(float)c.x : (float)c.x;
         const float c1 = (row & 512) ? -(float)c.y : (float)c.y;
         const float e0 = c0 - s0, e1 = c1 - s1;
         const float d0 = e0 * e0, d1 = e1 * e1;
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
         const float s0 = seq(0), s1 = V == 2 ? seq(1) : 0.f;
         if constexpr (HYB) {
 #pragma unroll
-            for (int j = tid; j < 1024; j += VT_NT) s_D[j] = hyb_error(j, s0, s1);
+            for (int j = tid; j < ROWS; j += VT_NT) s_D[j] = hyb_error(j, s0, s1);
             __syncthreads();
         }
 #pragma unroll
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
     for (int t = 1; t < G; t++) {
         if constexpr (HYB) {
 #pragma unroll
-            for (int j = tid; j < 1024; j += VT_NT) s_D[j] = hyb_error(j, seq(V * t), seq(V * t + 1));
+            for (int j = tid; j < ROWS; j += VT_NT) s_D[j] = hyb_error(j, seq(V * t), seq(V * t + 1));
         }
         if constexpr (Geo::LOCAL) {
             // prefix hi = NT h + tid; its predecessors p 2^OV + hi are registers p NB1 + h
@@ -413,7 +415,11 @@ size_t quantize_gpu_workspace(int k, int V, long tiles) {
 hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, const uint32_t *lut,
                                uint32_t *codes, float *tile_err, void *ws, size_t ws_bytes,
                                hipStream_t st) {
-    if (code_id == CODE_HYB) {
+    if (code_id == CODE_HYB2) {
+        if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB2>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB2>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<8, 2, CODE_HYB2>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+    } else if (code_id == CODE_HYB) {
         if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
         if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
         return quantize_gpu_t<8, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);

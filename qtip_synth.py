@@ -17,8 +17,8 @@ from dataclasses import dataclass, replace
 
 import numpy as np
 
-CODE_1MAD, CODE_3INST, CODE_HYB = 0, 1, 2
-CODE_NAMES = {CODE_1MAD: "1MAD", CODE_3INST: "3INST", CODE_HYB: "HYB"}
+CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2 = 0, 1, 2, 3
+CODE_NAMES = {CODE_1MAD: "1MAD", CODE_3INST: "3INST", CODE_HYB: "HYB", CODE_HYB2: "HYB2"}
 BASE_SEED = 240611235
 
 
@@ -107,7 +107,7 @@ def make_inputs(w, seed=None):
     if w.row_scale:
         row_scale = rng.uniform(0.5, 1.5, size=w.m).astype(np.float16)
     lut = None
-    if w.code_id == CODE_HYB:
+    if w.code_id in (CODE_HYB, CODE_HYB2):
         lut = rng.standard_normal(size=(1 << w.Q, 2)).astype(np.float16)
     X = rng.standard_normal(size=(w.B, w.n)).astype(np.float16)
     return Inputs(codes, signs_n, signs_m, row_scale, lut, X)

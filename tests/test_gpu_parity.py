@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 import qtip_synth as synth
-from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB
+from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2
 
 pytestmark = pytest.mark.gpu
 
@@ -62,7 +62,8 @@ def run_matmat(q, w, inp, use_matvec=False, scale=True):
 
 ALL_CODECS = [(CODE_3INST, 2, 1), (CODE_3INST, 3, 1), (CODE_3INST, 4, 1),
               (CODE_1MAD, 2, 1), (CODE_1MAD, 3, 1), (CODE_1MAD, 4, 1),
-              (CODE_HYB, 2, 2), (CODE_HYB, 3, 2), (CODE_HYB, 4, 2)]
+              (CODE_HYB, 2, 2), (CODE_HYB, 3, 2), (CODE_HYB, 4, 2),
+              (CODE_HYB2, 2, 2), (CODE_HYB2, 3, 2), (CODE_HYB2, 4, 2)]
 
 
 def small_workload(code_id, k, V, m, n, B=1, row_scale=False, sub=0):
@@ -73,11 +74,11 @@ def small_workload(code_id, k, V, m, n, B=1, row_scale=False, sub=0):
 
 # ------------------------------------------------------------------ the codes
 
-@pytest.mark.parametrize("code_id,V", [(CODE_1MAD, 1), (CODE_3INST, 1), (CODE_HYB, 2)])
+@pytest.mark.parametrize("code_id,V", [(CODE_1MAD, 1), (CODE_3INST, 1), (CODE_HYB, 2), (CODE_HYB2, 2)])
 def test_code_table_all_states_bit_exact(q, code_id, V):
     import torch
     rng = np.random.default_rng(42)
-    lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id == CODE_HYB else None
+    lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id in (CODE_HYB, CODE_HYB2) else None
     states = np.arange(65536, dtype=np.uint32)
     out = torch.zeros(65536 * V, dtype=torch.float16, device="cuda")
     q.qtip_decode_states(dev(states), 65536, 16, V, code_id, dev(lut), out)
@@ -101,7 +102,7 @@ def test_dequantize_small_bit_exact(q, code_id, k, V, m, n):
 
 def test_dequantize_special_streams(q):
     # all-zero and all-one streams, and a single set bit that wraps around the tile end
-    for code_id, k, V in [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 4, 2)]:
+    for code_id, k, V in [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 4, 2), (CODE_HYB2, 2, 2)]:
         w = small_workload(code_id, k, V, 32, 32)
         inp = synth.make_inputs(w)
         for fill in (0, 0xFFFFFFFF):

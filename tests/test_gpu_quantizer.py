@@ -12,13 +12,14 @@ import pytest
 
 import oracle
 import qtip_synth as synth
-from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB
+from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2
 
 pytestmark = pytest.mark.gpu
 
 ALL_CODECS = [(CODE_3INST, 2, 1), (CODE_3INST, 3, 1), (CODE_3INST, 4, 1),
               (CODE_1MAD, 2, 1), (CODE_1MAD, 3, 1), (CODE_1MAD, 4, 1),
-              (CODE_HYB, 2, 2), (CODE_HYB, 3, 2), (CODE_HYB, 4, 2)]
+              (CODE_HYB, 2, 2), (CODE_HYB, 3, 2), (CODE_HYB, 4, 2),
+              (CODE_HYB2, 2, 2), (CODE_HYB2, 3, 2), (CODE_HYB2, 4, 2)]
 
 
 @pytest.fixture(scope="module")
@@ -31,7 +32,7 @@ def q():
 
 
 def make_lut(code_id, rng):
-    return rng.standard_normal((512, 2)).astype(np.float16) if code_id == CODE_HYB else None
+    return rng.standard_normal((512, 2)).astype(np.float16) if code_id in (CODE_HYB, CODE_HYB2) else None
 
 
 def run_quantize_gpu(q, W, k, V, code_id, lut, tiles_in_flight=None):
@@ -70,7 +71,7 @@ def test_streams_and_values_equal_the_binary32_oracle(q, code_id, k, V):
 
 def test_decodable_weights_come_back_exactly(q):
     rng = np.random.default_rng(8)
-    for code_id, k, V in [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 2, 2)]:
+    for code_id, k, V in [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 2, 2), (CODE_HYB2, 4, 2)]:
         lut = make_lut(code_id, rng)
         m, n = 32, 48
         codes = rng.integers(0, 1 << 32, ((m // 16) * (n // 16), 8 * k), dtype=np.uint64).astype(np.uint32)
@@ -82,7 +83,7 @@ def test_decodable_weights_come_back_exactly(q):
 
 
 @pytest.mark.parametrize("code_id,k,V,name", [(CODE_3INST, 2, 1, "3INST"), (CODE_1MAD, 2, 1, "1MAD"),
-                                              (CODE_HYB, 2, 2, "HYB")])
+                                              (CODE_HYB, 2, 2, "HYB"), (CODE_HYB2, 2, 2, "HYB")])
 def test_gaussian_matrix_properties_and_table1(q, golden, code_id, k, V, name):
     """256 tiles of i.i.d. Gaussian weights scaled to the code: every reported error is the
     true distortion of the tile's own (tail-biting) stream, the mean squared error matches
@@ -108,7 +109,7 @@ def test_gaussian_matrix_properties_and_table1(q, golden, code_id, k, V, name):
     _, mse_host = q.qtip_quantize(W, m, n, 16, k, V, code_id, lut)
     assert abs(mse - mse_host) <= 2e-4 * mse_host     # near-ties may pick other walks
     rel = mse / sd ** 2
-    tol = 0.03 if code_id != CODE_HYB else 0.12
+    tol = 0.03 if code_id not in (CODE_HYB, CODE_HYB2) else 0.12
     assert abs(rel / t1[name] - 1) < tol, (name, rel)
     assert rel > t1["DR"]
 
