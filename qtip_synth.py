@@ -72,6 +72,7 @@ WORKLOADS = {w.name: w for w in [
     _w("cfg3_1mad_k3_4096x14336", 3, 4, 4096, 14336, CODE_1MAD, 3, 1, 2048, 2048),
     _w("cfg3_1mad_k4_4096x14336", 3, 5, 4096, 14336, CODE_1MAD, 4, 1, 2048, 2048),
     _w("cfg4_hyb_k2_8192x28672", 4, 0, 8192, 28672, CODE_HYB, 2, 2, 4096, 4096),
+    _w("next_hyb2_k2_8192x28672", 6, 0, 8192, 28672, CODE_HYB2, 2, 2, 4096, 4096),
     _w("cfg5_hyb_k4_8192x8192_b1", 5, 0, 8192, 8192, CODE_HYB, 4, 2, 4096, 4096, B=1),
     _w("cfg5_hyb_k4_8192x8192_b4", 5, 1, 8192, 8192, CODE_HYB, 4, 2, 4096, 4096, B=4),
     _w("cfg5_hyb_k4_8192x8192_b16", 5, 2, 8192, 8192, CODE_HYB, 4, 2, 4096, 4096, B=16),

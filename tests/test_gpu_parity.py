@@ -189,7 +189,7 @@ FULL = ["cfg1_3inst_k2_1024x1024", "cfg2_3inst_k2_4096x4096", "cfg3_1mad_k2_1433
         "cfg3_1mad_k3_14336x4096", "cfg3_1mad_k4_14336x4096", "cfg3_1mad_k2_4096x14336",
         "cfg3_1mad_k3_4096x14336", "cfg3_1mad_k4_4096x14336", "cfg4_hyb_k2_8192x28672",
         "cfg5_hyb_k4_8192x8192_b1", "cfg5_hyb_k4_8192x8192_b4", "cfg5_hyb_k4_8192x8192_b16",
-        "cfg5_hyb_k4_8192x8192_b64", "metric_3inst_k2_8192x28672"]
+        "cfg5_hyb_k4_8192x8192_b64", "metric_3inst_k2_8192x28672", "next_hyb2_k2_8192x28672"]
 
 
 def sample_rows(w, rng, count=48):
