@@ -27,10 +27,9 @@ int hip_fail(const char *what, hipError_t e) {
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-// Checks shared by every call that reads a code stream.
-int check_codec(const char *fn, const void *codes, int L, int k, int V, int code_id,
-                const void *lut, int m, int n) {
-    if (!codes) return fail(QTIP_EINVAL, "%s: codes is NULL", fn);
+// The (L, k, V, code) combinations that are built, the table the HYB codes need, and the
+// matrix shape: shared by every call that reads or writes a code stream.
+int check_code(const char *fn, int L, int k, int V, int code_id, const void *lut, int m, int n) {
     if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
         code_id != QTIP_CODE_HYB2)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
@@ -40,10 +39,18 @@ int check_codec(const char *fn, const void *codes, int L, int k, int V, int code
     if (V != wantV)
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d (code %d needs V = %d)", fn, V, code_id, wantV);
     if (is_hyb(code_id) && !lut) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (lut && !aligned(lut, 4)) return fail(QTIP_EINVAL, "%s: lut must be 4-byte aligned", fn);
     if (m <= 0 || n <= 0 || m % 16 || n % 16)
         return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    return QTIP_OK;
+}
+
+// The same for calls that read a code stream.
+int check_codec(const char *fn, const void *codes, int L, int k, int V, int code_id,
+                const void *lut, int m, int n) {
+    if (!codes) return fail(QTIP_EINVAL, "%s: codes is NULL", fn);
+    if (int rc = check_code(fn, L, k, V, code_id, lut, m, n)) return rc;
     if (!aligned(codes, 16)) return fail(QTIP_EINVAL, "%s: codes must be 16-byte aligned", fn);
-    if (lut && !aligned(lut, 4)) return fail(QTIP_EINVAL, "%s: lut must be 4-byte aligned", fn);
     return QTIP_OK;
 }
 
@@ -161,13 +168,7 @@ int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code
     const char *fn = "qtip_decode_states";
     if (!states || !out_f16) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (count < 0) return fail(QTIP_EINVAL, "%s: count = %d", fn, count);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
-        code_id != QTIP_CODE_HYB2)
-        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
-    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
-    if (V != (is_hyb(code_id) ? 2 : 1))
-        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
+    if (int rc = check_code(fn, L, /*k=*/2, V, code_id, lut_f16, 16, 16)) return rc;  // no k, no shape
     if (count == 0) return QTIP_OK;
     hipError_t e = qtip::launch_decode_states(code_id, states, count, (const uint32_t *)lut_f16,
                                               out_f16, (hipStream_t)stream);
@@ -179,16 +180,7 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
                   const void *lut_f16, uint32_t *codes_out, double *mse_out) {
     const char *fn = "qtip_quantize";
     if (!W || !codes_out) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
-        code_id != QTIP_CODE_HYB2)
-        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
-    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
-    if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
-    if (V != (is_hyb(code_id) ? 2 : 1))
-        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
-    if (m <= 0 || n <= 0 || m % 16 || n % 16)
-        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
     int rc;
     try {
         rc = qtip::quantize_host(W, m, n, k, V, code_id, (const uint16_t *)lut_f16, codes_out, mse_out);
@@ -211,16 +203,7 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
                       size_t workspace_bytes, void *stream) {
     const char *fn = "qtip_quantize_gpu";
     if (!W || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
-        code_id != QTIP_CODE_HYB2)
-        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
-    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
-    if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
-    if (V != (is_hyb(code_id) ? 2 : 1))
-        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
-    if (m <= 0 || n <= 0 || m % 16 || n % 16)
-        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
     if (((uintptr_t)W | (uintptr_t)codes_out | (uintptr_t)tile_err) % 4 || (uintptr_t)workspace % 256)
         return fail(QTIP_EINVAL, "%s: W, codes_out, tile_err need 4-byte, workspace 256-byte alignment", fn);
     if (workspace_bytes < qtip::quantize_gpu_workspace(k, V, 1))
@@ -262,16 +245,7 @@ int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int 
                        void *workspace, size_t workspace_bytes, void *stream) {
     const char *fn = "qtip_quantize_ldlq";
     if (!W || !A || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
-    if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
-        code_id != QTIP_CODE_HYB2)
-        return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
-    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
-    if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
-    if (V != (is_hyb(code_id) ? 2 : 1))
-        return fail(QTIP_EUNSUPPORTED, "%s: V = %d does not fit code %d", fn, V, code_id);
-    if (is_hyb(code_id) && !lut_f16) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
-    if (m <= 0 || n <= 0 || m % 16 || n % 16)
-        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
     if (((uintptr_t)W | (uintptr_t)A | (uintptr_t)codes_out | (uintptr_t)What_out | (uintptr_t)tile_err) % 4 ||
         (uintptr_t)workspace % 256)
         return fail(QTIP_EINVAL, "%s: arrays need 4-byte, workspace 256-byte alignment", fn);
