@@ -218,8 +218,9 @@ int qtip_block_ldl(const double *H, int n, float *A_out, double *D_out, void *wo
  *   workspace: 256-byte aligned; qtip_quantize_ldlq_workspace(m, n, k, V, t) bytes keep
  *   t tiles of a column block in flight (a block has m/16 tiles; t = m/16 is the most
  *   that helps; any t >= 1 works).
- * The feedback sum is binary32, terms added in ascending column order with one fused
- * multiply-add each, so that the input of the quantizer is reproducible.
+ * The feedback sum is binary32, one fused multiply-add per term, column blocks from the last
+ * one down and ascending inside a block, so that the input of the quantizer is reproducible.
+ * The workspace holds a running m x n fp32 sum besides the quantizer's own.
  */
 size_t qtip_quantize_ldlq_workspace(int m, int n, int k, int V, long tiles);
 int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int k, int V, int code_id,

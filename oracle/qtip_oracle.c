@@ -752,8 +752,11 @@ int orc_block_ldl(const double *H, int n, int g, double *Lout, double *Dout) {
  * (A = L - I is zero on and above its diagonal blocks, so the block's own
  * columns drop out of the paper's slice jT_y: ).  Binary32, in one fixed
  * order so that a GPU implementation can be followed decision by decision:
- * start from W[r][jg+c] and add the terms E[r][i] * A[i][jg+c] for
- * i = (j+1)g ... n-1 in ascending order, each with one fused multiply-add.
+ * start from W[r][jg+c] and add the terms E[r][i] * A[i][jg+c], one fused
+ * multiply-add each, taking the column blocks from the last one down to
+ * j+1 and the columns i inside a block in ascending order.  (The paper gives
+ * no order; this is the order in which a sum that is updated every time a
+ * block is finished receives its terms.)
  * E = W - What (m x n), A n x n, x m x g, all row-major float.
  */
 void orc_ldlq_feedback_f32(const float *W, const float *E, const float *A, int m, int n, int g,
@@ -762,8 +765,9 @@ void orc_ldlq_feedback_f32(const float *W, const float *E, const float *A, int m
     for (int r = 0; r < m; r++)
         for (int c = 0; c < g; c++) {
             float acc = W[(size_t)r * n + j * g + c];
-            for (int i = (j + 1) * g; i < n; i++)
-                acc = fmaf(E[(size_t)r * n + i], A[(size_t)i * n + j * g + c], acc);
+            for (int b = n / g - 1; b > j; b--)
+                for (int i = b * g; i < (b + 1) * g; i++)
+                    acc = fmaf(E[(size_t)r * n + i], A[(size_t)i * n + j * g + c], acc);
             x[(size_t)r * g + c] = acc;
         }
 }

@@ -209,7 +209,7 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
     if (workspace_bytes < qtip::quantize_gpu_workspace(k, V, 1))
         return fail(QTIP_EINVAL, "%s: workspace of %zu bytes cannot hold one tile (%zu needed)", fn,
                     workspace_bytes, qtip::quantize_gpu_workspace(k, V, 1));
-    hipError_t e = qtip::launch_quantize_gpu(k, code_id, W, m, n, (const uint32_t *)lut_f16, codes_out,
+    hipError_t e = qtip::launch_quantize_gpu(k, code_id, W, m, n, n, (const uint32_t *)lut_f16, codes_out,
                                              tile_err, workspace, workspace_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(fn, e);
     return QTIP_OK;

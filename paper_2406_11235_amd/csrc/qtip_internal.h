@@ -26,10 +26,10 @@ hipError_t launch_rht(const void *x, bool x_is_f32, const int8_t *signs, int n, 
 int quantize_host(const float *W, int m, int n, int k, int V, int code_id, const uint16_t *lut,
                   uint32_t *codes_out, double *mse_out);
 
-// GPU tail-biting Viterbi quantizer (qtip_viterbi.hip).  hipErrorInvalidValue if the
-// workspace cannot hold one sequence.
+// GPU tail-biting Viterbi quantizer (qtip_viterbi.hip).  W is m x n with row stride ld
+// (elements).  hipErrorInvalidValue if the workspace cannot hold one sequence.
 size_t quantize_gpu_workspace(int k, int V, long tiles);
-hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, const uint32_t *lut,
+hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, int ld, const uint32_t *lut,
                                uint32_t *codes, float *tile_err, void *ws, size_t ws_bytes,
                                hipStream_t st);
 

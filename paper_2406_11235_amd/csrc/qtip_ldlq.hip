@@ -9,8 +9,10 @@
 // lower triangle.  It is a one-off of n^3/3 multiply-adds per layer.
 //
 // The feedback sum is written so that a CPU reference can repeat it bit for bit, because
-// what it feeds is a quantizer, whose decisions are not continuous: binary32, the terms
-// E[r][i] A[i][c] added in ascending i, one fused multiply-add each, one thread per output.
+// what it feeds is a quantizer, whose decisions are not continuous: binary32, one fused
+// multiply-add per term E[r][i] A[i][c], the terms taken block by block from the last
+// column block down, ascending inside a block (the order in which a running sum that is
+// updated after every finished block receives them).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -105,28 +107,47 @@ __global__ void ldl_emit_kernel(const double *__restrict__ Lm, float *__restrict
 
 // ------------------------------------------------------------------ Algorithm 5
 
-// x[r][c] = W[r][16 j + c] + sum_{i = 16 (j+1)}^{n-1} E[r][i] A[i][16 j + c], ascending, fma.
-__global__ __launch_bounds__(256) void ldlq_feedback_kernel(const float *__restrict__ W,
-                                                            const float *__restrict__ E,
-                                                            const float *__restrict__ A, int m, int n,
-                                                            int j, float *__restrict__ x) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    const int r = idx / G, c = idx % G;
-    if (r >= m) return;
-    float acc = W[(size_t)r * n + j * G + c];
-    const float *e = E + (size_t)r * n;
-    const float *a = A + j * G + c;
-    for (int i = (j + 1) * G; i < n; i++) acc = __builtin_fmaf(e[i], a[(size_t)i * n], acc);
-    x[(size_t)r * G + c] = acc;
+// The feedback of Algorithm 5 as a running sum: X starts as W; when column block j is done,
+// its error E_j = (W - What)[:, 16j:16j+16] is fed to every column before it,
+//     X[r][c] += sum_{i in block j, ascending} E_j[r][i] A[16 j + i][c],   c < 16 j,
+// one fused multiply-add per term.  When block j's turn comes, X[:, 16j:16j+16] is its x.
+// Per element the terms arrive by blocks from the last one down and ascending inside a
+// block: that order is the definition both sides use.  A thread owns one column and 8 rows:
+// 16 values of A in registers, the rows' errors are wave-uniform.
+constexpr int UPD_ROWS = 8;
+__global__ __launch_bounds__(256) void ldlq_update_kernel(const float *__restrict__ Eslab,
+                                                          const float *__restrict__ A, int m, int n, int j,
+                                                          float *__restrict__ X) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int r0 = blockIdx.y * UPD_ROWS;
+    if (c >= j * G) return;
+    float a[G];
+#pragma unroll
+    for (int i = 0; i < G; i++) a[i] = A[(size_t)(j * G + i) * n + c];
+#pragma unroll
+    for (int rr = 0; rr < UPD_ROWS; rr++) {
+        const int r = r0 + rr;
+        if (r >= m) break;
+        float acc = X[(size_t)r * n + c];
+#pragma unroll
+        for (int i = 0; i < G; i++) acc = __builtin_fmaf(Eslab[(size_t)r * G + i], a[i], acc);
+        X[(size_t)r * n + c] = acc;
+    }
 }
 
-// After block j is quantized: E and What for its columns from the decoded slab, and the
+__global__ void ldlq_copy_kernel(const float *__restrict__ src, float *__restrict__ dst, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+// After block j is quantized: its error slab E_j and What from the decoded slab, and the
 // slab's codes and errors to their places in the matrix's tile order.
 __global__ __launch_bounds__(256) void ldlq_finish_kernel(const float *__restrict__ W,
                                                           const half_t *__restrict__ slab,
                                                           const uint32_t *__restrict__ slab_codes,
                                                           const float *__restrict__ slab_err, int m, int n,
-                                                          int j, int nwords, float *__restrict__ E,
+                                                          int j, int nwords, float *__restrict__ Eslab,
                                                           float *__restrict__ What,
                                                           uint32_t *__restrict__ codes,
                                                           float *__restrict__ tile_err) {
@@ -135,7 +156,7 @@ __global__ __launch_bounds__(256) void ldlq_finish_kernel(const float *__restric
     if (r >= m) return;
     const float w = (float)slab[(size_t)r * G + c];
     const size_t at = (size_t)r * n + j * G + c;
-    E[at] = W[at] - w;
+    Eslab[(size_t)r * G + c] = W[at] - w;
     if (What) What[at] = w;
     const int tn = n / G;
     if (idx < (m / G) * nwords) {
@@ -166,8 +187,8 @@ hipError_t launch_block_ldl(const double *H, int n, float *A, double *Dout, void
     return hipGetLastError();
 }
 
-// Workspace of the loop: E (m x n), x (m x 16), the decoded slab (fp16 m x 16), the slab's
-// codes and errors, then the Viterbi quantizer's own workspace.
+// Workspace of the loop: the running sum X (m x n), the error slab (m x 16), the decoded
+// slab (fp16 m x 16), the slab's codes and errors, then the Viterbi quantizer's own workspace.
 static size_t ldlq_fixed_bytes(int m, int n, int k) {
     return align256((size_t)m * n * 4) + align256((size_t)m * G * 4) + align256((size_t)m * G * 2) +
            align256((size_t)(m / G) * 8 * k * 4) + align256((size_t)(m / G) * 4);
@@ -183,9 +204,9 @@ hipError_t launch_quantize_ldlq(int k, int V, int code_id, const float *W, const
                                 void *ws, size_t ws_bytes, hipStream_t st) {
     (void)V;
     char *p = (char *)ws;
-    float *E = (float *)p;
+    float *X = (float *)p;
     p += align256((size_t)m * n * 4);
-    float *x = (float *)p;
+    float *Eslab = (float *)p;
     p += align256((size_t)m * G * 4);
     half_t *slab = (half_t *)p;
     p += align256((size_t)m * G * 2);
@@ -198,15 +219,20 @@ hipError_t launch_quantize_ldlq(int k, int V, int code_id, const float *W, const
     const size_t qbytes = ws_bytes - fixed;
     const int nwords = 8 * k;
     const dim3 egrid((m * G + 255) / 256);
+    hipLaunchKernelGGL(ldlq_copy_kernel, dim3(1024), dim3(256), 0, st, W, X, (size_t)m * n);
     for (int j = n / G - 1; j >= 0; j--) {
-        hipLaunchKernelGGL(ldlq_feedback_kernel, egrid, dim3(256), 0, st, W, (const float *)E, A, m, n, j, x);
-        hipError_t e = launch_quantize_gpu(k, code_id, x, m, G, lut, slab_codes, slab_err, p, qbytes, st);
+        // column block j of X is complete: quantize it in place (row stride n)
+        hipError_t e = launch_quantize_gpu(k, code_id, X + (size_t)j * G, m, G, n, lut, slab_codes, slab_err, p,
+                                           qbytes, st);
         if (e != hipSuccess) return e;
         e = launch_dequantize(k, code_id, slab_codes, lut, m, G, slab, st);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(ldlq_finish_kernel, egrid, dim3(256), 0, st, W, (const half_t *)slab,
-                           (const uint32_t *)slab_codes, (const float *)slab_err, m, n, j, nwords, E, What,
+                           (const uint32_t *)slab_codes, (const float *)slab_err, m, n, j, nwords, Eslab, What,
                            codes, tile_err);
+        if (j > 0)
+            hipLaunchKernelGGL(ldlq_update_kernel, dim3((j * G + 255) / 256, (m + UPD_ROWS - 1) / UPD_ROWS),
+                               dim3(256), 0, st, (const float *)Eslab, A, m, n, j, X);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -367,7 +367,7 @@ size_t head_bytes(long tiles) {
 }
 
 template <int KV, int V, int CODE>
-hipError_t quantize_gpu_t(const float *W, int m, int n, const uint32_t *lut, uint32_t *codes,
+hipError_t quantize_gpu_t(const float *W, int m, int n, int ld, const uint32_t *lut, uint32_t *codes,
                           float *tile_err, void *ws, size_t ws_bytes, hipStream_t st) {
     const int tn = n / 16;
     const long ntiles = (long)(m / 16) * tn;
@@ -383,11 +383,11 @@ hipError_t quantize_gpu_t(const float *W, int m, int n, const uint32_t *lut, uin
     for (long tile0 = 0; tile0 < ntiles; tile0 += cap) {
         const int cnt = (int)(ntiles - tile0 < cap ? ntiles - tile0 : cap);
         const dim3 bgrid((cnt + 63) / 64);
-        hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, n, tn,
+        hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, ld, tn,
                            tile0, lut, 1, (const uint32_t *)nullptr, ptrs, final_state, final_value);
         hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V>), bgrid, dim3(64), 0, st, ptrs, final_state,
                            final_value, cnt, 1, overlap, codes, tile_err, tile0);
-        hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, n, tn,
+        hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, ld, tn,
                            tile0, lut, 0, (const uint32_t *)overlap, ptrs, final_state, final_value);
         hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V>), bgrid, dim3(64), 0, st, ptrs, final_state,
                            final_value, cnt, 2, overlap, codes, tile_err, tile0);
@@ -412,25 +412,25 @@ size_t quantize_gpu_workspace(int k, int V, long tiles) {
     return head_bytes(tiles) + (size_t)tiles * (VT_T / V) * pw * sizeof(uint32_t);
 }
 
-hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, const uint32_t *lut,
+hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, int ld, const uint32_t *lut,
                                uint32_t *codes, float *tile_err, void *ws, size_t ws_bytes,
                                hipStream_t st) {
     if (code_id == CODE_HYB2) {
-        if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB2>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB2>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        return quantize_gpu_t<8, 2, CODE_HYB2>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB2>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB2>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<8, 2, CODE_HYB2>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
     } else if (code_id == CODE_HYB) {
-        if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        return quantize_gpu_t<8, 2, CODE_HYB>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<8, 2, CODE_HYB>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
     } else if (code_id == CODE_3INST) {
-        if (k == 2) return quantize_gpu_t<2, 1, CODE_3INST>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        if (k == 3) return quantize_gpu_t<3, 1, CODE_3INST>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        return quantize_gpu_t<4, 1, CODE_3INST>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 2) return quantize_gpu_t<2, 1, CODE_3INST>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<3, 1, CODE_3INST>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<4, 1, CODE_3INST>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
     } else {
-        if (k == 2) return quantize_gpu_t<2, 1, CODE_1MAD>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        if (k == 3) return quantize_gpu_t<3, 1, CODE_1MAD>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
-        return quantize_gpu_t<4, 1, CODE_1MAD>(W, m, n, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 2) return quantize_gpu_t<2, 1, CODE_1MAD>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<3, 1, CODE_1MAD>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<4, 1, CODE_1MAD>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
     }
 }
 

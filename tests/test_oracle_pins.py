@@ -550,13 +550,14 @@ def test_ldlq_feedback_is_the_stated_sum():
     Ai = (rng.integers(-4, 5, (n, n)) / 8.0).astype(np.float32)
     x = oracle.ldlq_feedback_f32(Wi, Ei, Ai, 1, g)
     assert np.array_equal(x, (Wi[:, g:2 * g] + Ei[:, 2 * g:].astype(np.float64) @ Ai[2 * g:, g:2 * g]).astype(np.float32))
-    # one fused multiply-add per term, ascending: repeated with numpy's float64 products
+    # one fused multiply-add per term, in the stated order: repeated with numpy's float64 products
     # rounded once (an fma of binary32 operands is the binary64 product and sum rounded once,
     # as long as the binary64 sum is exact enough: checked on a short row)
     r, c = 3, 5
     acc = np.float32(W[r, c])
-    for i in range(g, n):
-        acc = np.float32(np.float64(E[r, i]) * np.float64(A[i, c]) + np.float64(acc))
+    for b in range(n // g - 1, 0, -1):               # blocks from the last down, ascending inside
+        for i in range(b * g, (b + 1) * g):
+            acc = np.float32(np.float64(E[r, i]) * np.float64(A[i, c]) + np.float64(acc))
     assert abs(float(oracle.ldlq_feedback_f32(W, E, A, 0, g)[r, c]) - float(acc)) <= 2e-6 * abs(float(acc)) + 1e-6
 
 
