@@ -30,10 +30,10 @@ WORKLOAD = "metric_3inst_k2_8192x28672"
 # HBM bytes per launch of the decode + matvec kernel on this workload, from
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this file (summaries in
 # profiles/), scaled by what the same counters read for a plain copy of known size.
-# profiles/matvec_3inst_k2_8192x28672_traffic.txt: FETCH_SIZE 28944.1 KiB x 1.9998 (the copy kernel reads
+# profiles/matvec_3inst_k2_8192x28672_traffic.txt: FETCH_SIZE 28956.4 KiB x 1.9998 (the copy kernel reads
 # half of what it moves on this counter) + WRITE_SIZE 32.0 KiB x 1.0000.
-MEASURED_TRAFFIC_BYTES = {"metric_3inst_k2_8192x28672": 59304557}
-MEASURED_VALU_WAVE_INSTS = {"metric_3inst_k2_8192x28672": 20640000}
+MEASURED_TRAFFIC_BYTES = {"metric_3inst_k2_8192x28672": 59329719}
+MEASURED_VALU_WAVE_INSTS = {"metric_3inst_k2_8192x28672": 19548160}
 
 
 def log(*a):
