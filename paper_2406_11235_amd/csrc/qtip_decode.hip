@@ -151,12 +151,20 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
     __shared__ uint32_t s_lut[code_is_hyb(CODE) ? HYB_LDS_WORDS : 1];
     __shared__ float s_part[NW][16];
     __shared__ __attribute__((aligned(16))) half_t s_x[FUSED ? FUSED_MAX_N : 8];
-    __shared__ float s_v[FUSED ? rht_lds_floats(FUSED_MAX_N) : 1];
+    // room for FUSED_MAX_N values in blocks of any size, each block with its padding
+    __shared__ float s_v[FUSED ? FUSED_MAX_N + FUSED_MAX_N / 32 + FUSED_MAX_N / 16 : 1];
     if constexpr (FUSED) {
-        const int b = 1 << log2_block;
-        for (int o = 0; o < 16 * tn; o += b) {
-            half_t *dst = s_x + o;
-            rht_block<half_t, 0>(x + o, signs + o, log2_block, 0, s_v, threadIdx.x, NW * 64,
+        // groups of threads take one block each (a thread holds 16 values per round)
+        const int b = 1 << log2_block, n = 16 * tn;
+        const int gthreads = min(NW * 64, b >> 4);
+        const int groups = min(NW * 64 / gthreads, FUSED_MAX_N / b);  // what s_v holds
+        const int group = threadIdx.x / gthreads, gtid = threadIdx.x % gthreads;
+        for (int o0 = 0; o0 < n; o0 += groups * b) {
+            const int o = o0 + group * b;
+            const bool active = group < groups && o < n;
+            half_t *dst = s_x + (active ? o : 0);
+            rht_block<half_t, 0>(x + (active ? o : 0), signs + (active ? o : 0), log2_block, 0,
+                                 s_v + (active ? group : 0) * rht_lds_floats(b), gtid, gthreads, active,
                                  [dst](int idx, half_t v) { dst[idx] = v; });
         }
     }

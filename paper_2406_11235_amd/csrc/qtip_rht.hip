@@ -1,7 +1,9 @@
 // Random Hadamard transform of activations (Section 2.1 of arXiv 2406.11235):
 // a block-diagonal fast Walsh-Hadamard transform with +-1 sign vectors.
 //
-// One workgroup transforms one block of one batch row with rht_block (qtip_rht_device.h).
+// One workgroup of 256 threads transforms one block of 4096 or more values of one batch
+// row, or as many smaller blocks as make 4096 values (a thread holds 16 values per round),
+// with rht_block (qtip_rht_device.h).
 #include "qtip_device.h"
 #include "qtip_internal.h"
 #include "qtip_rht_device.h"
@@ -14,10 +16,17 @@ __global__ __launch_bounds__(256) void rht_kernel(const TIN *__restrict__ x,
                                                   const int8_t *__restrict__ signs, int n, int prt,
                                                   int side, half_t *__restrict__ out) {
     extern __shared__ float s_v[];
-    const int b = 1 << (PT > 0 ? PT : prt);
-    const size_t base = (size_t)blockIdx.y * n + (size_t)blockIdx.x * b;
+    const int p = PT > 0 ? PT : prt;
+    const int b = 1 << p;
+    // groups of b/16 threads, one block each, when the block is below 4096
+    const int gthreads = b >= 4096 ? 256 : b >> 4;
+    const int group = threadIdx.x / gthreads, gtid = threadIdx.x % gthreads;
+    const int blk = blockIdx.x * (256 / gthreads) + group;
+    const bool active = (size_t)blk * b < (size_t)n;
+    const size_t base = (size_t)blockIdx.y * n + (active ? (size_t)blk * b : 0);
     half_t *o = out + base;
-    rht_block<TIN, PT>(x + base, signs + (size_t)blockIdx.x * b, prt, side, s_v, threadIdx.x, 256,
+    rht_block<TIN, PT>(x + base, signs + (active ? (size_t)blk * b : 0), prt, side,
+                       s_v + group * rht_lds_floats(b), gtid, gthreads, active,
                        [o](int idx, half_t v) { o[idx] = v; });
 }
 
@@ -25,8 +34,9 @@ hipError_t launch_rht(const void *x, bool x_is_f32, const int8_t *signs, int n, 
                       int batch, int side, void *out, hipStream_t st) {
     int p = 0;
     while ((1 << p) < block) p++;
-    dim3 grid(n / block, batch);
-    const size_t lds = (size_t)rht_lds_floats(block) * sizeof(float);
+    const int per_wg = block >= 4096 ? 1 : 4096 / block;  // blocks per workgroup
+    dim3 grid((n / block + per_wg - 1) / per_wg, batch);
+    const size_t lds = (size_t)rht_lds_floats(block) * per_wg * sizeof(float);
 #define QTIP_RHT_LAUNCH(T, PT)                                                                   \
     hipLaunchKernelGGL((rht_kernel<T, PT>), grid, dim3(256), lds, st, (const T *)x, signs, n, p, \
                        side, (half_t *)out)

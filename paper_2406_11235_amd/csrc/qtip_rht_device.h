@@ -67,14 +67,17 @@ __device__ __forceinline__ void apply_signs16(const int8_t *sg, float (&v)[16]) 
     }
 }
 
-// One block of 2^p values: x (global) -> store(idx, fp16 value).  All `nthreads` threads of
-// the workgroup call it together (it synchronizes the workgroup after every round, the last
-// included).  PT > 0 fixes p at compile time (index arithmetic folds away); PT == 0 takes it
+// One block of 2^p values: x (global) -> store(idx, fp16 value).  A group of `nthreads`
+// threads (`tid` = 0 .. nthreads-1) works on one block; several groups of a workgroup may
+// work on different blocks, each with its own s_v, as long as EVERY thread of the workgroup
+// makes the call with the same p: it synchronizes the workgroup after every round, the last
+// included.  Threads with active = false only take part in the synchronization.  PT > 0 fixes p at compile time (index arithmetic folds away); PT == 0 takes it
 // from the argument.  sg: the block's signs.  side 0: V (S .* x); side 1: S .* (V^T x).
 // s_v: LDS scratch of 2^p floats, plus one per 32 when 2^p <= 8192.
 template <typename TIN, int PT, typename STORE>
 __device__ __forceinline__ void rht_block(const TIN *__restrict__ x, const int8_t *__restrict__ sg, int prt,
-                                          int side, float *s_v, int tid, int nthreads, STORE store) {
+                                          int side, float *s_v, int tid, int nthreads, bool active,
+                                          STORE store) {
     const int p = PT > 0 ? PT : prt;
     const int b = 1 << p;
     // 2^(-p/2) as an exact power of two times the correctly rounded 1/sqrt(2): the same bits
@@ -88,7 +91,7 @@ __device__ __forceinline__ void rht_block(const TIN *__restrict__ x, const int8_
         if (lo >= p) break;
         const int q = min(4, p - lo);
         const bool first = lo == 0, last = lo + q == p;
-        for (int u = tid; u < units; u += nthreads) {
+        for (int u = active ? tid : units; u < units; u += nthreads) {
             float v[16];
             if (first) {
                 // block >= 16, so the first round always owns bits 0..3: idx = 16u + e

@@ -258,6 +258,24 @@ def test_rht_against_explicit_matrix(q, block, side):
     assert torch.equal(out2, out) and torch.equal(xin, out)
 
 
+@pytest.mark.parametrize("block,nblk", [(16, 517), (64, 131), (256, 43), (1024, 9), (2048, 3)])
+def test_rht_many_small_blocks(q, block, nblk):
+    """Blocks below 4096 share a workgroup (as many as make 4096 values): block counts that
+    leave the last workgroup partly empty, both sides (11008 = 43 x 256 is a Llama width)."""
+    import torch
+    rng = np.random.default_rng(block + nblk)
+    n = block * nblk
+    x = rng.standard_normal((3, n)).astype(np.float16)
+    s = (rng.integers(0, 2, n) * 2 - 1).astype(np.int8)
+    for side in (0, 1):
+        ref = oracle.rht(x, s, block, side)
+        out = torch.full((3, n), float("nan"), dtype=torch.float16, device="cuda")
+        q.qtip_rht(dev(x), dev(s), n, block, 3, side, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref) <= 2.0 ** -11 * np.abs(ref) + 1e-5 * np.abs(ref).max())
+
+
 def test_full_layer_composition(q):
     """y = S_m V_m^T (scale .* (W~ (V_n S_n x))) on config 1, GPU end to end vs oracle."""
     import torch
