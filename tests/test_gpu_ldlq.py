@@ -150,3 +150,11 @@ def test_ldlq_error_codes(q):
     q.qtip_quantize_ldlq(W, A, 16, 32, 16, 2, 1, CODE_3INST, None, codes, None, None, ws, need)
     torch.cuda.synchronize()
     assert float(A.abs().max()) == 0.0          # H = I: no feedback
+
+
+def test_example_quantize_then_infer(q):
+    """The package's example: BlockLDLQ-quantize a synthetic layer on the GPU, then run the
+    inference path on the result; the codes decode to the quantizer's What and the fused
+    product agrees with the dense one."""
+    from paper_2406_11235_amd import example
+    assert example.main(256, 512, seed=3) < 2e-3
