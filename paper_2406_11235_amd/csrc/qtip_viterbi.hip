@@ -10,7 +10,8 @@
 // for the minimum: the 2^kV predecessors of y all end in the top 16-kV bits of y, so
 // states with a common "prefix" hi = y >> kV share one minimum, and the predecessors
 // p 2^(16-kV) + hi of a prefix have the same low 10 bits, i.e. live in one thread
-// (kV <= 6; for kV = 8 they are spread over four threads, which meet in LDS).  A step is
+// (kV <= 6; for kV = 8 they are spread over four threads, which meet in LDS; for kV <= 3 a
+// thread instead owns whole (predecessor, child) squares of states, see VitGeo).  A step is
 //   phase 1: every thread takes the minimum and arg-minimum over the predecessors of
 //            its prefixes, publishes the minima in LDS (2^(16-kV) floats, 64 KiB at
 //            kV = 2) and stores the arg-minima, kV bits each, packed into one or two
@@ -56,7 +57,14 @@ struct VitGeo {
     // back-pointers: kV bits per prefix, FPW whole fields per word, PWT words per thread
     static constexpr int FPW = 32 / KV;
     static constexpr int PWT = (NB1 + FPW - 1) / FPW;
-    static constexpr int PW = LOCAL ? VT_NT * PWT : NP;  // back-pointer words per step
+    // kV <= 3: a thread can own, for a few values "mid" of the middle 16 - 2 kV bits of the
+    // state, all 2^kV x 2^kV states (p, mid, c).  Then the predecessors of a prefix (mid, c)
+    // are still its own registers, and so are all 2^kV children of a prefix it reads back, so
+    // one LDS read serves 2^kV states and a thread's minima are contiguous in LDS (16-byte
+    // LDS operations).  SJ = mids per thread: mid = SJ tid + j.
+    static constexpr bool SLOT = VT_NT == 1024 && KV <= 3;
+    static constexpr int SJ = SLOT ? VT_REGS / (NC * NC) : 1;
+    static constexpr int PW = SLOT ? VT_NT : LOCAL ? VT_NT * PWT : NP;  // back-pointer words per step
 };
 
 __host__ __device__ constexpr int vit_max(int a, int b) { return a > b ? a : b; }
@@ -128,21 +136,32 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
     }
     __syncthreads();
     auto seq = [&](int u) -> float { return s_seq[u]; };
+    // the state held in register r: NT r + tid, or (p, SJ tid + j, c) with r = (p SJ + j) NC + c;
+    // increasing in r either way
+    auto state_of = [&](int r) -> uint32_t {
+        if constexpr (Geo::SLOT) {
+            const int p = r / (Geo::SJ * NC), j = (r / NC) % Geo::SJ, c = r % NC;
+            return ((uint32_t)p << Geo::OV) | ((uint32_t)(tid * Geo::SJ + j) << KV) | (uint32_t)c;
+        } else {
+            return (uint32_t)(r * VT_NT + tid);
+        }
+    };
 
     // code values of this thread's states
     half2_t cpk[HYB ? 1 : VT_REGS / 2];
     uint32_t ipk[HYB ? VT_REGS / 2 : 1];
 #pragma unroll
     for (int r = 0; r < VT_REGS; r++) {
-        const uint32_t y = (uint32_t)(r * VT_NT + tid);
+        const uint32_t y = state_of(r);
         if constexpr (HYB) {
             const uint32_t X = y * y + y;
             uint32_t row = (X >> (15 - HYB_Q)) & 1023u;  // table index and sign bit
             if constexpr (CODE == CODE_HYB2) row |= (X >> 31) << 10;  // second sign bit
+            // kept as the byte offset of the row's error in the per-step table
             if (r & 1)
-                ipk[r >> 1] |= row << 16;
+                ipk[r >> 1] |= (row * 4) << 16;
             else
-                ipk[r >> 1] = row;
+                ipk[r >> 1] = row * 4;
         } else {
             cpk[r >> 1][r & 1] = CODE == CODE_3INST ? code_3inst(y) : code_1mad(y);
         }
@@ -168,13 +187,47 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
         const float d0 = e0 * e0, d1 = e1 * e1;
         return d0 + d1;
     };
-    auto error = [&](int r, float s0) -> float {  // squared error of state r of this thread
+    // Squared errors of states 2 r2 and 2 r2 + 1 of this thread (they share a packed register).
+    // The unpacking is pinned here (volatile asm, one block per pair): hoisted out of the step
+    // loop it turns the 32 packed registers into 64 and the loop starts spilling, and the
+    // reloads cost far more than the unpacking (the waves run in lockstep between barriers,
+    // so nothing hides their latency).
+    auto errors2 = [&](int r2, float s0, float &d0, float &d1) {
         if constexpr (HYB) {
-            return s_D[(ipk[r >> 1] >> (16 * (r & 1))) & 0xFFFFu];
+            uint32_t o0, o1;  // byte offsets of the two rows' errors in the per-step table
+            asm volatile("v_and_b32 %0, 0xffff, %2\n\tv_lshrrev_b32 %1, 16, %2"
+                         : "=&v"(o0), "=v"(o1)
+                         : "v"(ipk[r2]));
+            d0 = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o0);
+            d1 = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o1);
         } else {
-            const float e = (float)cpk[r >> 1][r & 1] - s0;
-            return e * e;
+            // (two statements: measured faster than one block for both conversions, which in
+            // turn is the faster form for the table offsets above)
+            float c0, c1;
+            const uint32_t cw = as_u32(cpk[r2]);
+            asm volatile("v_cvt_f32_f16_e32 %0, %1" : "=v"(c0) : "v"(cw));
+            asm volatile("v_cvt_f32_f16_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1"
+                         : "=v"(c1)
+                         : "v"(cw));
+            const float e0 = c0 - s0, e1 = c1 - s0;
+            d0 = e0 * e0;
+            d1 = e1 * e1;
         }
+    };
+
+    // One state at a time (V = 1): the form the kV <= 3 layout runs fastest with (measured;
+    // the loops differ only in how the compiler schedules around the pinned conversions).
+    auto error1 = [&](int r, float s0) -> float {
+        float c;
+        const uint32_t cw = as_u32(cpk[r >> 1]);
+        if (r & 1)
+            asm volatile("v_cvt_f32_f16_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1"
+                         : "=v"(c)
+                         : "v"(cw));
+        else
+            asm volatile("v_cvt_f32_f16_e32 %0, %1" : "=v"(c) : "v"(cw));
+        const float e = c - s0;
+        return e * e;
     };
 
     const float INF = __builtin_inff();
@@ -190,10 +243,12 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
             __syncthreads();
         }
 #pragma unroll
-        for (int r = 0; r < VT_REGS; r++) {
-            const uint32_t y = (uint32_t)(r * VT_NT + tid);
-            const float d = error(r, s0);
-            val[r] = (constrained && (y >> KV) != O) ? INF : d;
+        for (int r2 = 0; r2 < VT_REGS / 2; r2++) {
+            float d[2];
+            errors2(r2, s0, d[0], d[1]);
+#pragma unroll
+            for (int h = 0; h < 2; h++)
+                val[2 * r2 + h] = (constrained && (state_of(2 * r2 + h) >> KV) != O) ? INF : d[h];
         }
         if constexpr (HYB) __syncthreads();
     }
@@ -204,7 +259,24 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
 #pragma unroll
             for (int j = tid; j < ROWS; j += VT_NT) s_D[j] = hyb_error(j, seq(V * t), seq(V * t + 1));
         }
-        if constexpr (Geo::LOCAL) {
+        if constexpr (Geo::SLOT) {
+            // prefix hi = (SJ tid + j) NC + c; its predecessors are registers (p SJ + j) NC + c
+            constexpr int F = Geo::SJ * NC;  // prefixes per thread, contiguous in hi
+            float bests[F];
+            uint32_t word = 0;
+#pragma unroll
+            for (int f = 0; f < F; f++) {
+                uint32_t bp;
+                argmin_regs<NC, 1>(val, f, F, bests[f], bp);
+                word |= bp << (f * KV);
+                if ((f & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int f = 0; f < F; f += 4)
+                *reinterpret_cast<float4_t *>(&s_best[tid * F + f]) =
+                    float4_t{bests[f], bests[f + 1], bests[f + 2], bests[f + 3]};
+            my_ptrs[(size_t)t * PW + tid] = word;
+        } else if constexpr (Geo::LOCAL) {
             // prefix hi = NT h + tid; its predecessors p 2^OV + hi are registers p NB1 + h
             uint32_t word[Geo::PWT];
 #pragma unroll
@@ -253,16 +325,40 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
         // (read after the barrier, so that the errors are not computed, and kept in
         // registers that are not there, before the minima)
         const float s0 = HYB ? 0.f : seq(t);
+        if constexpr (Geo::SLOT) {
+            // states (p, mid, c') follow prefix (p, mid): one read per (p, j) serves NC states
+#pragma unroll
+            for (int p = 0; p < NC; p++) {
+                float b[Geo::SJ];
+                if constexpr (Geo::SJ == 4) {
+                    const float4_t t4 = *reinterpret_cast<const float4_t *>(&s_best[p * (NP / NC) + tid * 4]);
+                    b[0] = t4[0], b[1] = t4[1], b[2] = t4[2], b[3] = t4[3];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < Geo::SJ; j++) b[j] = s_best[p * (NP / NC) + tid * Geo::SJ + j];
+                }
+#pragma unroll
+                for (int j = 0; j < Geo::SJ; j++)
+#pragma unroll
+                    for (int c = 0; c < NC; c++) {
+                        const int r = (p * Geo::SJ + j) * NC + c;
+                        val[r] = b[j] + error1(r, s0);
+                    }
+                if (((p * Geo::SJ) & 1) == 1 || Geo::SJ > 1) __builtin_amdgcn_sched_barrier(0);
+            }
+        } else
         // eight states at a time: the register file has no room for 64 loads in flight
 #pragma unroll
         for (int r0 = 0; r0 < VT_REGS; r0 += 8) {
 #pragma unroll
-            for (int r = r0; r < r0 + 8; r++) {
-                // prefix of state NT r + tid; written so that the address is one base
-                // register plus a constant
-                const float b = best_mine[r * (VT_NT >> KV)];
-                const float d = error(r, s0);
-                val[r] = b + d;
+            for (int r = r0; r < r0 + 8; r += 2) {
+                // prefixes of states NT r + tid and NT (r + 1) + tid; written so that the
+                // addresses are one base register plus constants
+                const float b0 = best_mine[r * (VT_NT >> KV)], b1 = best_mine[(r + 1) * (VT_NT >> KV)];
+                float d0, d1;
+                errors2(r / 2, s0, d0, d1);
+                val[r] = b0 + d0;
+                val[r + 1] = b1 + d1;
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -274,7 +370,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
     uint32_t by = 0xFFFFFFFFu;
 #pragma unroll
     for (int r = 0; r < VT_REGS; r++) {
-        const uint32_t y = (uint32_t)(r * VT_NT + tid);
+        const uint32_t y = state_of(r);
         const bool ok = !constrained || (y & (uint32_t)(NP - 1)) == O;
         if (ok && val[r] < bv) {
             bv = val[r];
@@ -334,7 +430,11 @@ __global__ __launch_bounds__(64) void viterbi_backtrace_kernel(
         if (t == stop) break;
         const uint32_t hi = arg >> KV;
         uint32_t p;
-        if constexpr (Geo::LOCAL) {
+        if constexpr (Geo::SLOT) {
+            constexpr uint32_t F = Geo::SJ * NC;  // prefix hi is field hi % F of thread hi / F
+            const uint32_t word = my_ptrs[(size_t)t * PW + hi / F];
+            p = (word >> ((hi % F) * KV)) & (uint32_t)(NC - 1);
+        } else if constexpr (Geo::LOCAL) {
             const uint32_t h = hi / VT_NT;
             const uint32_t word = my_ptrs[(size_t)t * PW + (h / Geo::FPW) * VT_NT + (hi & (VT_NT - 1))];
             p = (word >> ((h % Geo::FPW) * KV)) & (uint32_t)(NC - 1);
