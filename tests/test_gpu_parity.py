@@ -131,7 +131,7 @@ def test_matvec_small(q, code_id, k, V, m, n):
 
 
 @pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
-@pytest.mark.parametrize("B", [1, 3, 4, 16, 17, 40, 64, 80])
+@pytest.mark.parametrize("B", [1, 3, 4, 8, 9, 15, 16, 17, 40, 64, 80])
 def test_matmat_small_with_row_scale(q, code_id, k, V, B):
     m, n = 64, 1104
     w = small_workload(code_id, k, V, m, n, B=B, row_scale=True, sub=B)
