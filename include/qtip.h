@@ -176,8 +176,8 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
  *               qtip_quantize_gpu_workspace(k, V, t) for t of a few thousand (about
  *               1 MiB per tile at V = 1, 0.5 MiB or less at V = 2) to keep the
  *               device full.  Contents are scratch.
- * The search runs in binary32 with one rounding per operation (error e = c - s,
- * squared errors summed left to right, value = minimum over predecessors + error),
+ * The search runs in binary32 with fixed roundings (e = c - s; V = 1: value =
+ * fma(e, e, minimum over predecessors); V = 2: value = minimum + fma(e1, e1, e0*e0)),
  * lowest predecessor and lowest final state on ties; the paper does not fix a
  * precision.  Streams therefore equal a binary32 CPU search bit for bit, and may
  * differ from a binary64 search where two walks tie to within rounding.

@@ -506,10 +506,13 @@ double orc_tailbiting_quantize(const double *S, int T, int L, int k, int V, cons
  * that keeps its value function in single precision: the paper does not fix
  * the precision of the search, and a different precision can decide
  * near-ties differently, so both sides take the decisions in this one.
- * Every operation is a single correctly rounded binary32 operation, in this
- * order (no fused multiply-add; the file is built with contraction off):
- *   e_j = C[y][j] - S[V t + j];  d = e_0*e_0  (V = 1)  or  (e_0*e_0) + (e_1*e_1)  (V = 2);
- *   value(y) = min over predecessors + d.
+ * The operations, each correctly rounded to binary32, are exactly these (the
+ * file is built with contraction off; fmaf is the fused multiply-add):
+ *   e_j = C[y][j] - S[V t + j];
+ *   V = 1: value(y) = fmaf(e_0, e_0, min over predecessors)   (first step: e_0*e_0)
+ *   V = 2: value(y) = (min over predecessors) + fmaf(e_1, e_1, e_0*e_0)
+ * (the form a GPU takes: one fused operation per state for V = 1, a per-step
+ * table of the 2^(Q+1) possible errors for the V = 2 codes).
  * Minima and ties are as in orc_viterbi.  V <= 2.
  */
 float orc_viterbi_f32(const float *S, int T, int L, int k, int V, const float *C,
@@ -535,8 +538,7 @@ float orc_viterbi_f32(const float *S, int T, int L, int k, int V, const float *C
             float d = e0 * e0;
             if (V == 2) {
                 float e1 = C[(size_t)y * V + 1] - S[V * t + 1];
-                float d1 = e1 * e1;
-                d = d + d1;
+                d = fmaf(e1, e1, d);
             }
             if (t == 0) {
                 if (first_top >= 0 && (y >> kV) != (uint32_t)first_top) d = INFINITY;
@@ -552,7 +554,7 @@ float orc_viterbi_f32(const float *S, int T, int L, int k, int V, const float *C
                     arg = x;
                 }
             }
-            nxt[y] = best + d;
+            nxt[y] = V == 1 ? fmaf(e0, e0, best) : best + d;
             back[(size_t)t * NS + y] = arg;
         }
         float *tmp = val;

@@ -26,8 +26,10 @@
 // Algorithm 4 is forward / walk-to-the-middle / constrained forward / full walk.
 //
 // Arithmetic (fixed, so that a CPU reference can repeat every decision): binary32,
-// one rounding per operation, no fused multiply-add:
-//   e_j = C[y][j] - s[V t + j];  d = e_0 e_0  or  (e_0 e_0) + (e_1 e_1);  value = min + d.
+//   e_j = C[y][j] - s[V t + j];
+//   V = 1: value = fma(e_0, e_0, min)            (the first step: e_0 e_0)
+//   V = 2: value = min + fma(e_1, e_1, e_0 e_0)  (the error comes from a per-step table)
+// with exactly these roundings (the file is compiled without contraction).
 // Minima take the lowest predecessor on ties, the final state the lowest state.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -184,50 +186,46 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
         const float c0 = (row & 1024) ? -(float)c.x : (float)c.x;
         const float c1 = (row & 512) ? -(float)c.y : (float)c.y;
         const float e0 = c0 - s0, e1 = c1 - s1;
-        const float d0 = e0 * e0, d1 = e1 * e1;
-        return d0 + d1;
+        return __builtin_fmaf(e1, e1, e0 * e0);
     };
-    // Squared errors of states 2 r2 and 2 r2 + 1 of this thread (they share a packed register).
-    // The unpacking is pinned here (volatile asm, one block per pair): hoisted out of the step
-    // loop it turns the 32 packed registers into 64 and the loop starts spilling, and the
-    // reloads cost far more than the unpacking (the waves run in lockstep between barriers,
-    // so nothing hides their latency).
-    auto errors2 = [&](int r2, float s0, float &d0, float &d1) {
+    // New values of states 2 r2 and 2 r2 + 1 of this thread (they share a packed register)
+    // from the minima b0, b1 of their prefixes: fma(e, e, b) for V = 1, b + table entry for
+    // HYB.  The unpacking is pinned here (volatile asm): hoisted out of the step loop it turns
+    // the 32 packed registers into 64 and the loop starts spilling, and the reloads cost far
+    // more than the unpacking (the waves run in lockstep between barriers, so nothing hides
+    // their latency).  For V = 1 the conversion and the subtraction are one v_fma_mix_f32,
+    // (float)c * 1.0 - s: an exact product and one rounding, the same bits as c - s.
+    auto update2 = [&](int r2, float s0, float b0, float b1, float &v0, float &v1) {
         if constexpr (HYB) {
             uint32_t o0, o1;  // byte offsets of the two rows' errors in the per-step table
             asm volatile("v_and_b32 %0, 0xffff, %2\n\tv_lshrrev_b32 %1, 16, %2"
                          : "=&v"(o0), "=v"(o1)
                          : "v"(ipk[r2]));
-            d0 = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o0);
-            d1 = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o1);
+            v0 = b0 + *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o0);
+            v1 = b1 + *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o1);
         } else {
-            // (two statements: measured faster than one block for both conversions, which in
-            // turn is the faster form for the table offsets above)
-            float c0, c1;
             const uint32_t cw = as_u32(cpk[r2]);
-            asm volatile("v_cvt_f32_f16_e32 %0, %1" : "=v"(c0) : "v"(cw));
-            asm volatile("v_cvt_f32_f16_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1"
-                         : "=v"(c1)
-                         : "v"(cw));
-            const float e0 = c0 - s0, e1 = c1 - s0;
-            d0 = e0 * e0;
-            d1 = e1 * e1;
+            float e0, e1;
+            asm volatile("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,0]"
+                         : "=v"(e0) : "v"(cw), "v"(s0));
+            asm volatile("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+                         : "=v"(e1) : "v"(cw), "v"(s0));
+            v0 = __builtin_fmaf(e0, e0, b0);
+            v1 = __builtin_fmaf(e1, e1, b1);
         }
     };
-
     // One state at a time (V = 1): the form the kV <= 3 layout runs fastest with (measured;
-    // the loops differ only in how the compiler schedules around the pinned conversions).
-    auto error1 = [&](int r, float s0) -> float {
-        float c;
+    // the loops differ only in how the compiler schedules around the pinned instructions).
+    auto update1 = [&](int r, float s0, float b) -> float {
         const uint32_t cw = as_u32(cpk[r >> 1]);
+        float e;
         if (r & 1)
-            asm volatile("v_cvt_f32_f16_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1"
-                         : "=v"(c)
-                         : "v"(cw));
+            asm volatile("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+                         : "=v"(e) : "v"(cw), "v"(s0));
         else
-            asm volatile("v_cvt_f32_f16_e32 %0, %1" : "=v"(c) : "v"(cw));
-        const float e = c - s0;
-        return e * e;
+            asm volatile("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,0]"
+                         : "=v"(e) : "v"(cw), "v"(s0));
+        return __builtin_fmaf(e, e, b);
     };
 
     const float INF = __builtin_inff();
@@ -245,7 +243,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
 #pragma unroll
         for (int r2 = 0; r2 < VT_REGS / 2; r2++) {
             float d[2];
-            errors2(r2, s0, d[0], d[1]);
+            update2(r2, s0, 0.f, 0.f, d[0], d[1]);  // the first step has no predecessors
 #pragma unroll
             for (int h = 0; h < 2; h++)
                 val[2 * r2 + h] = (constrained && (state_of(2 * r2 + h) >> KV) != O) ? INF : d[h];
@@ -342,7 +340,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
 #pragma unroll
                     for (int c = 0; c < NC; c++) {
                         const int r = (p * Geo::SJ + j) * NC + c;
-                        val[r] = b[j] + error1(r, s0);
+                        val[r] = update1(r, s0, b[j]);
                     }
                 if (((p * Geo::SJ) & 1) == 1 || Geo::SJ > 1) __builtin_amdgcn_sched_barrier(0);
             }
@@ -355,10 +353,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
                 // prefixes of states NT r + tid and NT (r + 1) + tid; written so that the
                 // addresses are one base register plus constants
                 const float b0 = best_mine[r * (VT_NT >> KV)], b1 = best_mine[(r + 1) * (VT_NT >> KV)];
-                float d0, d1;
-                errors2(r / 2, s0, d0, d1);
-                val[r] = b0 + d0;
-                val[r + 1] = b1 + d1;
+                update2(r / 2, s0, b0, b1, val[r], val[r + 1]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }

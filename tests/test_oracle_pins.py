@@ -457,30 +457,45 @@ def test_viterbi_f32_near_exhaustive_optimum(L, k, V, T):
         assert abs(float(d32) - true) <= 1e-5 * true + 1e-7
 
 
-def test_viterbi_f32_operation_order_single_step():
-    """One trellis step (T = V): the value is min_y fl(fl(e0*e0) + fl(e1*e1)), every
-    operation rounded to binary32 on its own, which numpy's float32 scalars reproduce;
-    a fused multiply-add or binary64 intermediates give other bits on this sample."""
+def _fma32(a, b, c):
+    """fl32(a*b + c) for float32 a, b, c: the product of two 24-bit significands and the sum are
+    exact in the 64-bit significand of a long double for the magnitudes used here, so rounding
+    that once to float32 is the fused multiply-add."""
+    return np.float32(np.longdouble(a) * np.longdouble(b) + np.longdouble(c))
+
+
+def test_viterbi_f32_operation_order():
+    """The stated roundings, repeated with numpy: V = 2, one step: min_y fl(fma(e1, e1, fl(e0*e0)));
+    V = 1, two steps on a trellis whose every state follows every state (L = kV): the second
+    value is fma(e, e, min of the first), the first is fl(e*e).  Unfused or binary64 arithmetic
+    gives other bits on these samples (counted)."""
+    assert np.finfo(np.longdouble).nmant >= 63
     rng = np.random.default_rng(9)
     L = 10
     C = rng.standard_normal((1 << L, 2)).astype(np.float16).astype(np.float32)
-    hits = 0
-    for _ in range(50):
+    differs = 0
+    for _ in range(30):
         S = rng.standard_normal(2).astype(np.float32)
         e = C - S[None, :]
-        sq = e * e                                     # float32 products
-        d = sq[:, 0] + sq[:, 1]
-        want, arg = d.min(), int(d.argmin())
+        d = np.array([_fma32(e[y, 1], e[y, 1], e[y, 0] * e[y, 0]) for y in range(1 << L)], dtype=np.float32)
         got, st = oracle.viterbi_f32(S, L, 2, 2, C)
-        assert got == want and st[0] == arg
-        exact = ((C.astype(np.float64) - S.astype(np.float64)[None, :]) ** 2).sum(1)[arg]
-        hits += int(np.float32(exact) != want)
-    assert hits > 0          # the sample does distinguish rounding orders
-    C1 = C[:, :1].copy()
-    S1 = rng.standard_normal(1).astype(np.float32)
-    e = C1[:, 0] - S1[0]
-    got, st = oracle.viterbi_f32(S1, L, 2, 1, C1)
-    assert got == (e * e).min() and st[0] == int((e * e).argmin())
+        assert got == d.min() and st[0] == int(d.argmin())
+        unfused = (e[:, 0] * e[:, 0] + e[:, 1] * e[:, 1]).min()
+        differs += int(unfused != got)
+    assert differs > 0
+    # V = 1, L = kV = 4: the minimum over predecessors is the minimum over all states
+    C1 = rng.standard_normal((16, 1)).astype(np.float16).astype(np.float32)
+    differs = 0
+    for _ in range(200):
+        S1 = rng.standard_normal(2).astype(np.float32)
+        e0 = C1[:, 0] - S1[0]
+        first = (e0 * e0).min()
+        e1 = C1[:, 0] - S1[1]
+        second = np.array([_fma32(e1[y], e1[y], first) for y in range(16)], dtype=np.float32)
+        got, st = oracle.viterbi_f32(S1, 4, 4, 1, C1)
+        assert got == second.min() and st[1] == int(second.argmin()) and st[0] == int((e0 * e0).argmin())
+        differs += int((first + e1 * e1).min() != got)
+    assert differs > 0
 
 
 def test_tailbiting_f32_stream_is_cyclic_and_close_to_f64():
