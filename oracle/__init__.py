@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qtip_oracle.c")
 _LIB = os.path.join(_HERE, "libqtip_oracle.so")
 
-CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2 = 0, 1, 2, 3
+CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT = 0, 1, 2, 3, 4
 
 
 def build(force=False):
@@ -66,6 +66,13 @@ def lib():
         L.orc_decode_sequence_table.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         L.orc_dequantize.restype = i32
         L.orc_dequantize.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, vp]
+        L.orc_dequantize_tiled.restype = i32
+        L.orc_dequantize_tiled.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, vp]
+        L.orc_decode_element_tiled.restype = c.c_uint16
+        L.orc_decode_element_tiled.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32]
+        L.orc_decode_matmat_rows_tiled.restype = None
+        L.orc_decode_matmat_rows_tiled.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, vp,
+                                                   i32, vp, vp, i32, vp]
         L.orc_decode_element.restype = c.c_uint16
         L.orc_decode_element.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32]
         L.orc_matmat_dense.restype = None
@@ -200,21 +207,23 @@ def decode_sequence_table(words, T, L, k, V, C):
     return out, st
 
 
-def dequantize(codes, L, k, V, code_id, m, n, lut=None, Q=9):
-    """Dense decoded weights as uint16 fp16 bit patterns, shape (m, n)."""
+def dequantize(codes, L, k, V, code_id, m, n, lut=None, Q=9, tile=(16, 16)):
+    """Dense decoded weights as uint16 fp16 bit patterns, shape (m, n); tile = (T_x, T_y)."""
+    Tx, Ty = tile
     codes = _u32(codes).reshape(-1)
-    assert codes.size == (m // 16) * (n // 16) * 8 * k
+    assert codes.size == (m // Tx) * (n // Ty) * 8 * k
     lut = None if lut is None else _u16(lut).reshape(-1)
     W = np.zeros((m, n), dtype=np.uint16)
-    rc = lib().orc_dequantize(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, _p(W))
+    rc = lib().orc_dequantize_tiled(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, Tx, Ty, _p(W))
     assert rc == 0
     return W
 
 
-def decode_element(codes, L, k, V, code_id, n, i, j, lut=None, Q=9):
+def decode_element(codes, L, k, V, code_id, n, i, j, lut=None, Q=9, tile=(16, 16)):
     codes = _u32(codes).reshape(-1)
     lut = None if lut is None else _u16(lut).reshape(-1)
-    return int(lib().orc_decode_element(_p(codes), L, k, V, code_id, _p(lut), Q, n, i, j))
+    return int(lib().orc_decode_element_tiled(_p(codes), L, k, V, code_id, _p(lut), Q, n, tile[0], tile[1],
+                                              i, j))
 
 
 def matmat_dense(W, X, scale=None):
@@ -229,7 +238,7 @@ def matmat_dense(W, X, scale=None):
     return Y
 
 
-def decode_matmat_rows(codes, L, k, V, code_id, m, n, X, rows, lut=None, Q=9, scale=None):
+def decode_matmat_rows(codes, L, k, V, code_id, m, n, X, rows, lut=None, Q=9, scale=None, tile=(16, 16)):
     """fp64 outputs for the chosen rows only: shape (B, len(rows))."""
     codes = _u32(codes).reshape(-1)
     lut = None if lut is None else _u16(lut).reshape(-1)
@@ -238,8 +247,8 @@ def decode_matmat_rows(codes, L, k, V, code_id, m, n, X, rows, lut=None, Q=9, sc
     rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
     scale = _u16(scale)
     Y = np.zeros((B, rows.size), dtype=np.float64)
-    lib().orc_decode_matmat_rows(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, _p(X), B,
-                                 _p(scale), _p(rows), rows.size, _p(Y))
+    lib().orc_decode_matmat_rows_tiled(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, tile[0], tile[1],
+                                       _p(X), B, _p(scale), _p(rows), rows.size, _p(Y))
     return Y
 
 

@@ -13,9 +13,11 @@
  *     trellis (Section 3.1; Figure 1; tail-biting wrap, Section 3.2);
  *   - the state -> value codes 1MAD (Algorithm 1), 3INST (Algorithm 2) and
  *     HYB (Algorithm 3) and its two-sign-flip form, plus a plain table code
- *     C[2^L][V] (Section 2.3);
- *   - decode of a 16x16 tile and of a whole matrix (Section 4: a T_x x T_y
- *     block is one sequence; Algorithm 5's reshape gives the order);
+ *     C[2^L][V] (Section 2.3) and the lookup-only code of the appendix on
+ *     lookup-only codes (a stored fp16 table of 2^L entries, V = 1);
+ *   - decode of a tile and of a whole matrix (Section 4: a T_x x T_y
+ *     block is one sequence; Algorithm 5's reshape gives the order), for
+ *     16 x 16 tiles and, in the _tiled functions, any T_x T_y = 256;
  *   - dense fp64 matrix-vector / matrix-matrix product with the decoded
  *     weights;
  *   - the random Hadamard transform with an explicit Sylvester matrix
@@ -33,7 +35,7 @@
  * in 32-bit word i/32 at bit position 31-(i%32).  A matrix is a row-major
  * array of 16x16 tiles, tile (I,J) at index I*(n/16)+J, each tile k*T/32
  * words.  Sequence element s of a tile is matrix element (16I + s/16,
- * 16J + s%16).
+ * 16J + s%16); with T_x x T_y tiles, (T_x I + s/T_y, T_y J + s%T_y).
  *
  * Parity pins live in tests/test_oracle_pins.py.  Unpinned by the paper and
  * fixed by this build's reading: which HYB entry the sign bit flips (the
@@ -52,6 +54,7 @@
 #define ORC_CODE_3INST 1
 #define ORC_CODE_HYB 2
 #define ORC_CODE_HYB2 3
+#define ORC_CODE_LUT 4 /* lookup-only: the value of a state is table entry [state] */
 
 int orc_threads(void) {
 #ifdef _OPENMP
@@ -195,6 +198,8 @@ static void orc_code_eval(int code_id, uint32_t state, const uint16_t *lut, int 
         out[0] = orc_code_3inst(state);
     else if (code_id == ORC_CODE_HYB2)
         orc_code_hyb2(state, Q, lut, out);
+    else if (code_id == ORC_CODE_LUT)
+        out[0] = lut[state]; /* Section 2.3's plain table, 2^L fp16 entries (V = 1) */
     else
         orc_code_hyb(state, Q, lut, out);
 }
@@ -239,39 +244,52 @@ void orc_decode_sequence_table(const uint32_t *words, int T, int L, int k, int V
 }
 
 /*
- * Decode a whole m x n matrix stored as 16x16 tiles into dense row-major fp16
- * bit patterns W[m][n] (no row scale).
+ * Decode a whole m x n matrix stored as Tx x Ty tiles (Tx rows of the output
+ * dimension, Ty columns of the input dimension, Tx Ty = 256; Section 4) into
+ * dense row-major fp16 bit patterns W[m][n] (no row scale).  Tile (I, J) is
+ * sequence I (n/Ty) + J; its element s is matrix element (Tx I + s / Ty,
+ * Ty J + s % Ty), the order Algorithm 5's reshape of an m x Ty slab gives.
  */
-int orc_dequantize(const uint32_t *codes, int L, int k, int V, int code_id,
-                   const uint16_t *lut, int Q, int m, int n, uint16_t *W) {
-    if (m % 16 || n % 16) return -1;
+int orc_dequantize_tiled(const uint32_t *codes, int L, int k, int V, int code_id,
+                         const uint16_t *lut, int Q, int m, int n, int Tx, int Ty, uint16_t *W) {
+    if (Tx * Ty != 256 || m % Tx || n % Ty) return -1;
     const int T = 256;
     int wpt = k * T / 32; /* words per tile */
-    int tn = n / 16;
+    int tn = n / Ty;
 #pragma omp parallel for schedule(static)
-    for (int I = 0; I < m / 16; I++) {
+    for (int I = 0; I < m / Tx; I++) {
         uint16_t seq[256];
         for (int J = 0; J < tn; J++) {
             const uint32_t *tile = codes + ((size_t)I * tn + J) * wpt;
             orc_decode_sequence(tile, T, L, k, V, code_id, lut, Q, seq);
             for (int s = 0; s < T; s++)
-                W[(size_t)(16 * I + s / 16) * n + (16 * J + s % 16)] = seq[s];
+                W[(size_t)(Tx * I + s / Ty) * n + (Ty * J + s % Ty)] = seq[s];
         }
     }
     return 0;
 }
 
+int orc_dequantize(const uint32_t *codes, int L, int k, int V, int code_id,
+                   const uint16_t *lut, int Q, int m, int n, uint16_t *W) {
+    return orc_dequantize_tiled(codes, L, k, V, code_id, lut, Q, m, n, 16, 16, W);
+}
+
 /* Decoded weight (i, j) alone, straight from the stream. */
-uint16_t orc_decode_element(const uint32_t *codes, int L, int k, int V, int code_id,
-                            const uint16_t *lut, int Q, int n, int i, int j) {
+uint16_t orc_decode_element_tiled(const uint32_t *codes, int L, int k, int V, int code_id,
+                                  const uint16_t *lut, int Q, int n, int Tx, int Ty, int i, int j) {
     const int T = 256;
     int wpt = k * T / 32;
-    const uint32_t *tile = codes + ((size_t)(i / 16) * (n / 16) + (j / 16)) * wpt;
-    int s = 16 * (i % 16) + (j % 16);
+    const uint32_t *tile = codes + ((size_t)(i / Tx) * (n / Ty) + (j / Ty)) * wpt;
+    int s = Ty * (i % Tx) + (j % Ty);
     uint32_t st = orc_state(tile, k * T, L, k * V, s / V);
     uint16_t v[2];
     orc_code_eval(code_id, st, lut, Q, v);
     return v[s % V];
+}
+
+uint16_t orc_decode_element(const uint32_t *codes, int L, int k, int V, int code_id,
+                            const uint16_t *lut, int Q, int n, int i, int j) {
+    return orc_decode_element_tiled(codes, L, k, V, code_id, lut, Q, n, 16, 16, i, j);
 }
 
 /* ------------------------------------------------------------ dense product */
@@ -299,10 +317,10 @@ void orc_matmat_dense(const uint16_t *W, int m, int n, const uint16_t *X, int B,
  * The same product for a chosen set of output rows, decoding each needed
  * weight on its own: Y[b][r] for r in rows[0..nrows).  Y is B x nrows.
  */
-void orc_decode_matmat_rows(const uint32_t *codes, int L, int k, int V, int code_id,
-                            const uint16_t *lut, int Q, int m, int n, const uint16_t *X,
-                            int B, const uint16_t *scale, const int *rows, int nrows,
-                            double *Y) {
+void orc_decode_matmat_rows_tiled(const uint32_t *codes, int L, int k, int V, int code_id,
+                                  const uint16_t *lut, int Q, int m, int n, int Tx, int Ty,
+                                  const uint16_t *X, int B, const uint16_t *scale, const int *rows,
+                                  int nrows, double *Y) {
     (void)m;
 #pragma omp parallel for schedule(dynamic)
     for (int r = 0; r < nrows; r++) {
@@ -310,7 +328,7 @@ void orc_decode_matmat_rows(const uint32_t *codes, int L, int k, int V, int code
         double *wrow = (double *)malloc(sizeof(double) * (size_t)n);
         for (int j = 0; j < n; j++)
             wrow[j] = orc_f16_to_f64(
-                orc_decode_element(codes, L, k, V, code_id, lut, Q, n, i, j));
+                orc_decode_element_tiled(codes, L, k, V, code_id, lut, Q, n, Tx, Ty, i, j));
         for (int b = 0; b < B; b++) {
             double acc = 0.0;
             for (int j = 0; j < n; j++) acc += wrow[j] * orc_f16_to_f64(X[(size_t)b * n + j]);
@@ -319,6 +337,14 @@ void orc_decode_matmat_rows(const uint32_t *codes, int L, int k, int V, int code
         }
         free(wrow);
     }
+}
+
+void orc_decode_matmat_rows(const uint32_t *codes, int L, int k, int V, int code_id,
+                            const uint16_t *lut, int Q, int m, int n, const uint16_t *X,
+                            int B, const uint16_t *scale, const int *rows, int nrows,
+                            double *Y) {
+    orc_decode_matmat_rows_tiled(codes, L, k, V, code_id, lut, Q, m, n, 16, 16, X, B, scale, rows,
+                                 nrows, Y);
 }
 
 /* ---------------------------------------------------------------- Hadamard */

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import CODE_1MAD, CODE_3INST, CODE_HYB
+from oracle import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_LUT
 
 
 def _bits_to_words(bits):
@@ -75,7 +75,8 @@ def test_fig1_worked_example(golden):
 
 @pytest.mark.parametrize("L,k,V,T", [(16, 2, 1, 256), (16, 3, 1, 256), (16, 4, 1, 256),
                                       (16, 2, 2, 256), (16, 4, 2, 256), (5, 1, 1, 12),
-                                      (12, 2, 1, 64)])
+                                      (12, 2, 1, 64), (14, 2, 1, 256), (14, 3, 1, 256),
+                                      (14, 4, 1, 256)])
 def test_state_window_invariants(L, k, V, T):
     rng = np.random.default_rng(L * 100 + k * 10 + V)
     kV, nbits, G = k * V, k * T, T // V
@@ -227,6 +228,39 @@ def test_dequantize_tile_placement(code_id, k, V):
                                   seq.reshape(16, 16))
     for (i, j) in [(0, 0), (17, 33), (47, 63), (31, 16)]:
         assert oracle.decode_element(codes, 16, k, V, code_id, n, i, j, lut) == W[i, j]
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_lookup_only_code_on_32x8_tiles(k):
+    """The lookup-only code of the appendix (L = 14, V = 1, T_x = 32, T_y = 8): every step of
+    the decode written out here in Python and numpy, from the stream's bits to the matrix."""
+    rng = np.random.default_rng(140 + k)
+    L, Tx, Ty, m, n = 14, 32, 8, 64, 40
+    lut = rng.standard_normal(1 << L).astype(np.float16)
+    ntiles = (m // Tx) * (n // Ty)
+    codes = rng.integers(0, 1 << 32, (ntiles, 8 * k), dtype=np.uint64).astype(np.uint32)
+    seqs = np.zeros((ntiles, 256), dtype=np.uint16)
+    for tile in range(ntiles):
+        bits = "".join(format(int(w), "032b") for w in codes[tile])  # first bit = MSB of word 0
+        assert len(bits) == 256 * k
+        for t in range(256):
+            window = "".join(bits[(t * k + i) % len(bits)] for i in range(L))
+            seqs[tile, t] = lut.view(np.uint16)[int(window, 2)]
+    # Algorithm 5's reshape: an m x T_y slab becomes m/T_x sequences of T_x T_y values, row-major;
+    # slab J of tile row I is sequence I (n / T_y) + J
+    expect = seqs.reshape(m // Tx, n // Ty, Tx, Ty).transpose(0, 2, 1, 3).reshape(m, n)
+    W = oracle.dequantize(codes, L, k, 1, CODE_LUT, m, n, lut, tile=(Tx, Ty))
+    assert np.array_equal(W, expect)
+    for (i, j) in [(0, 0), (31, 7), (32, 8), (63, 39), (17, 22)]:
+        assert oracle.decode_element(codes, L, k, 1, CODE_LUT, n, i, j, lut, tile=(Tx, Ty)) == expect[i, j]
+    X = rng.standard_normal((2, n)).astype(np.float16)
+    rows = [0, 31, 32, 63, 5]
+    Y = oracle.decode_matmat_rows(codes, L, k, 1, CODE_LUT, m, n, X, rows, lut, tile=(Tx, Ty))
+    ref = X.astype(np.float64) @ expect.view(np.float16).astype(np.float64)[rows].T
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-12)
+    # the same table as an explicit codebook
+    C = oracle.codebook(L, 1, CODE_LUT, lut)
+    assert np.array_equal(C[:, 0], lut.astype(np.float64))
 
 
 def test_all_zero_stream_decodes_to_code_of_zero():
