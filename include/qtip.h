@@ -66,6 +66,8 @@ extern "C" {
 #define QTIP_CODE_HYB2 3  /* the same with bit 31 of the hash also XORed (Section 3.1.2): the first
                              entry gets a sign of its own; for L = 16 that bit is set exactly when
                              the state is at least 46341 */
+#define QTIP_CODE_LUT 4   /* lookup-only code (appendix on lookup-only codes): L = 14, V = 1, the value
+                             of a state is entry [state] of a stored table; T_x = 32, T_y = 8 */
 
 /*
  * Random Hadamard transform of activations (Section 2.1: W~ = V_m S_m W S_n V_n^T,

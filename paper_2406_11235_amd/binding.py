@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2 = 0, 1, 2, 3
+CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # QTIP_LIBRARY points at another build of the same library (e.g. to compare two builds)

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqtip.so")
-SOURCES = ["qtip_api.hip", "qtip_decode.hip", "qtip_rht.hip", "qtip_viterbi.hip", "qtip_ldlq.hip", "qtip_quantize.cpp"]
+SOURCES = ["qtip_api.hip", "qtip_decode.hip", "qtip_lut14.hip", "qtip_rht.hip", "qtip_viterbi.hip", "qtip_ldlq.hip", "qtip_quantize.cpp"]
 HEADERS = ["qtip_device.h", "qtip_rht_device.h", "qtip_internal.h", os.path.join("..", "..", "include", "qtip.h")]
 
 # Packed-FP32 VALU forms are switched off for every device compile.

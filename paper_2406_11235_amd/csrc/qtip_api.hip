@@ -10,6 +10,7 @@
 namespace {
 
 bool is_hyb(int code_id) { return code_id == QTIP_CODE_HYB || code_id == QTIP_CODE_HYB2; }
+bool is_lut(int code_id) { return code_id == QTIP_CODE_LUT; }
 
 thread_local char g_err[512] = "";
 
@@ -31,17 +32,22 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 // matrix shape: shared by every call that reads or writes a code stream.
 int check_code(const char *fn, int L, int k, int V, int code_id, const void *lut, int m, int n) {
     if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
-        code_id != QTIP_CODE_HYB2)
+        code_id != QTIP_CODE_HYB2 && code_id != QTIP_CODE_LUT)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
-    if (L != 16) return fail(QTIP_EUNSUPPORTED, "%s: L = %d (only L = 16 is built)", fn, L);
+    const int wantL = is_lut(code_id) ? 14 : 16;
+    if (L != wantL)
+        return fail(QTIP_EUNSUPPORTED, "%s: L = %d (code %d is built for L = %d)", fn, L, code_id, wantL);
     if (k < 2 || k > 4) return fail(QTIP_EUNSUPPORTED, "%s: k = %d (supported: 2, 3, 4)", fn, k);
     const int wantV = is_hyb(code_id) ? 2 : 1;
     if (V != wantV)
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d (code %d needs V = %d)", fn, V, code_id, wantV);
-    if (is_hyb(code_id) && !lut) return fail(QTIP_EINVAL, "%s: HYB code needs a lut", fn);
-    if (lut && !aligned(lut, 4)) return fail(QTIP_EINVAL, "%s: lut must be 4-byte aligned", fn);
-    if (m <= 0 || n <= 0 || m % 16 || n % 16)
-        return fail(QTIP_EINVAL, "%s: m = %d, n = %d must be positive multiples of 16", fn, m, n);
+    if ((is_hyb(code_id) || is_lut(code_id)) && !lut) return fail(QTIP_EINVAL, "%s: code %d needs a lut", fn, code_id);
+    if (lut && !aligned(lut, is_lut(code_id) ? 16 : 4))
+        return fail(QTIP_EINVAL, "%s: lut must be %d-byte aligned", fn, is_lut(code_id) ? 16 : 4);
+    // a sequence is a T_x x T_y block of the matrix: 32 x 8 for the lookup-only code, else 16 x 16
+    const int tx = is_lut(code_id) ? 32 : 16, ty = is_lut(code_id) ? 8 : 16;
+    if (m <= 0 || n <= 0 || m % tx || n % ty)
+        return fail(QTIP_EINVAL, "%s: m = %d must be a positive multiple of %d, n = %d of %d", fn, m, tx, n, ty);
     return QTIP_OK;
 }
 
@@ -115,14 +121,14 @@ int qtip_rht_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_
     hipError_t e;
     // one launch pays while there is at most one workgroup (tile row) per CU; with more, every
     // CU would redo the transform several times over
-    if (n <= qtip::fused_rht_matvec_max_n() && m <= 16 * 256) {
+    if (!is_lut(code_id) && n <= qtip::fused_rht_matvec_max_n() && m <= 16 * 256) {
         e = qtip::launch_rht_matvec(k, code_id, codes, (const uint32_t *)lut_f16, m, n, x_f16, signs_n, block,
                                     row_scale_f16, y, (hipStream_t)stream);
     } else {
         if (!xt_scratch_f16 || !aligned(xt_scratch_f16, 16))
             return fail(QTIP_EINVAL,
-                        "%s: n = %d above %d or m = %d above 4096: xt_scratch (n fp16, 16-byte aligned) is "
-                        "needed", fn, n, qtip::fused_rht_matvec_max_n(), m);
+                        "%s: n = %d above %d, m = %d above 4096 or the lookup-only code: xt_scratch (n fp16, "
+                        "16-byte aligned) is needed", fn, n, qtip::fused_rht_matvec_max_n(), m);
         e = qtip::launch_rht(x_f16, false, signs_n, n, block, 1, 0, xt_scratch_f16, (hipStream_t)stream);
         if (e == hipSuccess)
             e = qtip::launch_matvec(k, code_id, codes, (const uint32_t *)lut_f16, m, n, xt_scratch_f16,
@@ -168,7 +174,7 @@ int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code
     const char *fn = "qtip_decode_states";
     if (!states || !out_f16) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (count < 0) return fail(QTIP_EINVAL, "%s: count = %d", fn, count);
-    if (int rc = check_code(fn, L, /*k=*/2, V, code_id, lut_f16, 16, 16)) return rc;  // no k, no shape
+    if (int rc = check_code(fn, L, /*k=*/2, V, code_id, lut_f16, 32, 16)) return rc;  // no k, no shape
     if (count == 0) return QTIP_OK;
     hipError_t e = qtip::launch_decode_states(code_id, states, count, (const uint32_t *)lut_f16,
                                               out_f16, (hipStream_t)stream);
@@ -181,6 +187,7 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
     const char *fn = "qtip_quantize";
     if (!W || !codes_out) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
+    if (is_lut(code_id)) return fail(QTIP_EUNSUPPORTED, "%s: the lookup-only code is not built here", fn);
     int rc;
     try {
         rc = qtip::quantize_host(W, m, n, k, V, code_id, (const uint16_t *)lut_f16, codes_out, mse_out);
@@ -204,6 +211,7 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
     const char *fn = "qtip_quantize_gpu";
     if (!W || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
+    if (is_lut(code_id)) return fail(QTIP_EUNSUPPORTED, "%s: the lookup-only code is not built here", fn);
     if (((uintptr_t)W | (uintptr_t)codes_out | (uintptr_t)tile_err) % 4 || (uintptr_t)workspace % 256)
         return fail(QTIP_EINVAL, "%s: W, codes_out, tile_err need 4-byte, workspace 256-byte alignment", fn);
     if (workspace_bytes < qtip::quantize_gpu_workspace(k, V, 1))
@@ -246,6 +254,7 @@ int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int 
     const char *fn = "qtip_quantize_ldlq";
     if (!W || !A || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
+    if (is_lut(code_id)) return fail(QTIP_EUNSUPPORTED, "%s: the lookup-only code is not built here", fn);
     if (((uintptr_t)W | (uintptr_t)A | (uintptr_t)codes_out | (uintptr_t)What_out | (uintptr_t)tile_err) % 4 ||
         (uintptr_t)workspace % 256)
         return fail(QTIP_EINVAL, "%s: arrays need 4-byte, workspace 256-byte alignment", fn);

@@ -14,27 +14,6 @@
 
 namespace qtip {
 
-template <int K> struct Words;
-template <> struct Words<2> { uint32_t v[4]; };
-template <> struct Words<3> { uint32_t v[3]; };
-template <> struct Words<4> { uint32_t v[4]; };
-
-// This lane's WPL words of tile `tile` (q = lane's position inside the tile).
-template <int K>
-__device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ codes, size_t tile,
-                                               int q) {
-    constexpr int WPL = Geo<K>::WPL;
-    const uint32_t *p = codes + tile * (8 * K) + q * WPL;
-    Words<K> r;
-    if constexpr (WPL == 4) {
-        const uint4 t = *reinterpret_cast<const uint4 *>(p);
-        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
-    } else {
-        r.v[0] = p[0]; r.v[1] = p[1]; r.v[2] = p[2];
-    }
-    return r;
-}
-
 // The same plus the first word of the next lane of the same tile (cyclically: the
 // tail-biting wrap of Section 3.2).
 template <int K>
@@ -560,11 +539,13 @@ static hipError_t launch_matmat_t(const uint32_t *codes, const uint32_t *lut, in
 
 hipError_t launch_dequantize(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
                              int n, void *W, hipStream_t st) {
+    if (code_id == CODE_LUT) return launch_lut_dequantize(k, codes, lut, m, n, W, st);
     QTIP_DISPATCH(launch_dequantize_t, codes, lut, m, n, W, st);
 }
 
 hipError_t launch_matvec(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
                          int n, const void *x, const void *scale, float *y, hipStream_t st) {
+    if (code_id == CODE_LUT) return launch_lut_matvec(k, codes, lut, m, n, x, scale, y, st);
     QTIP_DISPATCH(launch_matvec_t, codes, lut, m, n, x, (const int8_t *)nullptr, 0, scale, y, st);
 }
 
@@ -581,12 +562,14 @@ hipError_t launch_rht_matvec(int k, int code_id, const uint32_t *codes, const ui
 hipError_t launch_matmat(int k, int code_id, const uint32_t *codes, const uint32_t *lut, int m,
                          int n, const void *X, int B, const void *scale, float *Y,
                          hipStream_t st) {
+    if (code_id == CODE_LUT) return launch_lut_matmat(k, codes, lut, m, n, X, B, scale, Y, st);
     QTIP_DISPATCH(launch_matmat_t, codes, lut, m, n, X, B, scale, Y, st);
 }
 
 hipError_t launch_decode_states(int code_id, const uint32_t *states, int count,
                                 const uint32_t *lut, void *out, hipStream_t st) {
     const int blocks = (count + 255) / 256;
+    if (code_id == CODE_LUT) return launch_lut_decode_states(states, count, lut, out, st);
     if (code_id == CODE_HYB2)
         hipLaunchKernelGGL((decode_states_kernel<CODE_HYB2>), dim3(blocks), dim3(256), 0, st, states,
                            count, lut, (half_t *)out);

@@ -32,6 +32,7 @@ constexpr int CODE_1MAD = 0;
 constexpr int CODE_3INST = 1;
 constexpr int CODE_HYB = 2;
 constexpr int CODE_HYB2 = 3;  // HYB with a second sign flip (bit 31 of the hash on the first entry)
+constexpr int CODE_LUT = 4;   // lookup-only: L = 14, V = 1, 32 x 8 blocks (kernels in qtip_lut14.hip)
 __host__ __device__ constexpr bool code_is_hyb(int code) { return code == CODE_HYB || code == CODE_HYB2; }
 
 // Section 3.1.1 constants.
@@ -48,6 +49,27 @@ template <int K> struct Geo;
 template <> struct Geo<2> { static constexpr int WPL = 4, LPT = 4, RPL = 4; };
 template <> struct Geo<3> { static constexpr int WPL = 3, LPT = 8, RPL = 2; };
 template <> struct Geo<4> { static constexpr int WPL = 4, LPT = 8, RPL = 2; };
+
+template <int K> struct Words;
+template <> struct Words<2> { uint32_t v[4]; };
+template <> struct Words<3> { uint32_t v[3]; };
+template <> struct Words<4> { uint32_t v[4]; };
+
+// This lane's WPL words of tile `tile` (q = lane's position inside the tile).
+template <int K>
+__device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ codes, size_t tile,
+                                               int q) {
+    constexpr int WPL = Geo<K>::WPL;
+    const uint32_t *p = codes + tile * (8 * K) + q * WPL;
+    Words<K> r;
+    if constexpr (WPL == 4) {
+        const uint4 t = *reinterpret_cast<const uint4 *>(p);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+        r.v[0] = p[0]; r.v[1] = p[1]; r.v[2] = p[2];
+    }
+    return r;
+}
 
 __device__ __forceinline__ half2_t as_half2(uint32_t v) {
     return __builtin_bit_cast(half2_t, v);

@@ -22,6 +22,16 @@ hipError_t launch_decode_states(int code_id, const uint32_t *states, int count,
 hipError_t launch_rht(const void *x, bool x_is_f32, const int8_t *signs, int n, int block,
                       int batch, int side, void *out, hipStream_t st);
 
+// The lookup-only code (qtip_lut14.hip): L = 14, V = 1, 32 x 8 blocks, lut = 2^14 fp16 values.
+hipError_t launch_lut_dequantize(int k, const uint32_t *codes, const void *lut, int m, int n, void *W,
+                                 hipStream_t st);
+hipError_t launch_lut_matvec(int k, const uint32_t *codes, const void *lut, int m, int n, const void *x,
+                             const void *scale, float *y, hipStream_t st);
+hipError_t launch_lut_matmat(int k, const uint32_t *codes, const void *lut, int m, int n, const void *X,
+                             int B, const void *scale, float *Y, hipStream_t st);
+hipError_t launch_lut_decode_states(const uint32_t *states, int count, const void *lut, void *out,
+                                    hipStream_t st);
+
 // Host-only tail-biting Viterbi quantizer (qtip_quantize.cpp).
 int quantize_host(const float *W, int m, int n, int k, int V, int code_id, const uint16_t *lut,
                   uint32_t *codes_out, double *mse_out);

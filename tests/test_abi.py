@@ -62,6 +62,13 @@ def test_argument_errors_need_no_gpu(q):
         (L.qtip_decode_matvec(p, 16, 2, 2, 2, None, 16, 16, p, p, None), EINVAL),
         (L.qtip_decode_matvec(p, 16, 2, 1, 7, None, 16, 16, p, p, None), EUNSUP),
         (L.qtip_decode_matvec(p + 4, 16, 2, 1, 1, None, 16, 16, p, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 16, 2, 1, 4, p, 32, 16, p, p, None), EUNSUP),       # the lookup-only code: L = 14
+        (L.qtip_decode_matvec(p, 14, 2, 1, 4, None, 32, 16, p, p, None), EINVAL),   # needs its table
+        (L.qtip_decode_matvec(p, 14, 2, 1, 4, p + 4, 32, 16, p, p, None), EINVAL),  # 16-byte aligned
+        (L.qtip_decode_matvec(p, 14, 2, 1, 4, p, 16, 16, p, p, None), EINVAL),      # 32 x 8 blocks
+        (L.qtip_decode_matvec(p, 14, 2, 1, 4, p, 32, 12, p, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 14, 2, 2, 4, p, 32, 16, p, p, None), EUNSUP),
+        (L.qtip_dequantize(p, 14, 5, 1, 4, p, 32, 16, p, None), EUNSUP),
         (L.qtip_decode_matmat(p, 16, 2, 1, 1, None, 16, 16, p, 0, None, p, None), EINVAL),
         (L.qtip_decode_matmat(p, 16, 2, 1, 1, None, 16, 16, p, 4, None, None, None), EINVAL),
         (L.qtip_dequantize(p, 16, 2, 1, 1, None, 16, 16, None, None), EINVAL),
@@ -97,7 +104,7 @@ def test_argument_errors_need_no_gpu(q):
     ]
     for i, (rc, want) in enumerate(cases):
         assert rc == want, (i, rc, want, q.qtip_last_error())
-    assert "multiples of 16" in q.qtip_last_error()
+    assert "multiple of 16" in q.qtip_last_error()
     assert L.qtip_decode_states(p, 0, 16, 1, 0, None, p, None) == 0     # empty input: no launch
     # workspace sizes: about 1 MiB of back-pointers per tile at V = 1, monotone in tiles
     w1, w2 = q.qtip_quantize_gpu_workspace(2, 1, 1), q.qtip_quantize_gpu_workspace(2, 1, 2)

@@ -1,0 +1,208 @@
+"""GPU parity for the lookup-only code (L = 14, V = 1, a stored table of 2^14 fp16 values,
+32 x 8 blocks): decode, batch-1 product, batched product on the matrix cores and the layer
+call, through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars as for the other codes: decoded fp16 weights bit-exact; products within max relative
+error 2e-3 of the fp64 oracle, measured as max|y - y*| / max|y*|."""
+import numpy as np
+import pytest
+
+import oracle
+import qtip_synth as synth
+from qtip_synth import CODE_LUT
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 2e-3
+OBSERVED_TOL = 1e-4
+TILE = (32, 8)
+
+
+@pytest.fixture(scope="module")
+def q():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2406_11235_amd as q
+    q.lib()
+    return q
+
+
+def dev(a):
+    import torch
+    if a is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_err(got, ref):
+    return float(np.abs(got - ref).max() / np.abs(ref).max())
+
+
+def workload(k, m, n, B=1, row_scale=False, sub=0):
+    return synth.Workload(f"small_LUT14_k{k}_{m}x{n}_b{B}", 9, 400 + 10 * k + sub, m, n, CODE_LUT, k, 1, 16, 16,
+                          B=B, row_scale=row_scale, L=14)
+
+
+def run_dequantize(q, w, inp):
+    import torch
+    W = torch.empty((w.m, w.n), dtype=torch.float16, device="cuda")
+    q.qtip_dequantize(dev(inp.codes), w.L, w.k, w.V, w.code_id, dev(inp.lut), w.m, w.n, W)
+    torch.cuda.synchronize()
+    return W.cpu().numpy().view(np.uint16)
+
+
+def run_matmat(q, w, inp, use_matvec=False, scale=True):
+    import torch
+    Y = torch.full((w.B, w.m), float("nan"), dtype=torch.float32, device="cuda")
+    codes, lut, X = dev(inp.codes), dev(inp.lut), dev(inp.X)
+    sc = dev(inp.row_scale) if scale else None
+    if use_matvec:
+        assert w.B == 1 and sc is None
+        q.qtip_decode_matvec(codes, w.L, w.k, w.V, w.code_id, lut, w.m, w.n, X, Y)
+    else:
+        q.qtip_decode_matmat(codes, w.L, w.k, w.V, w.code_id, lut, w.m, w.n, X, w.B, sc, Y)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy().astype(np.float64)
+
+
+def ref_weights(w, inp):
+    return oracle.dequantize(inp.codes, 14, w.k, 1, CODE_LUT, w.m, w.n, inp.lut, tile=TILE)
+
+
+def test_every_state_reads_its_table_entry(q):
+    import torch
+    rng = np.random.default_rng(14)
+    lut = rng.standard_normal(1 << 14).astype(np.float16)
+    states = np.arange(1 << 14, dtype=np.uint32)
+    out = torch.empty(1 << 14, dtype=torch.float16, device="cuda")
+    q.qtip_decode_states(dev(states), states.size, 14, 1, CODE_LUT, dev(lut), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), lut.view(np.uint16))
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+@pytest.mark.parametrize("m,n", [(32, 8), (96, 1080), (160, 2072)])
+def test_dequantize_small_bit_exact(q, k, m, n):
+    w = workload(k, m, n)
+    inp = synth.make_inputs(w)
+    assert np.array_equal(run_dequantize(q, w, inp), ref_weights(w, inp))
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_dequantize_special_streams(q, k):
+    # all-zero and all-one streams, and single set bits around the block's end (the wrap)
+    m, n = 32, 24
+    w = workload(k, m, n)
+    inp = synth.make_inputs(w)
+    for fill in (0, 0xFFFFFFFF):
+        inp.codes[:] = fill
+        assert np.array_equal(run_dequantize(q, w, inp), ref_weights(w, inp))
+    for word, bit in [(8 * k - 1, 0), (8 * k - 1, 5), (0, 31), (0, 20), (3, 16)]:
+        inp.codes[:] = 0
+        inp.codes[1, word] = np.uint32(1 << bit)
+        assert np.array_equal(run_dequantize(q, w, inp), ref_weights(w, inp))
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+@pytest.mark.parametrize("m,n", [(32, 8), (96, 1080), (160, 4104), (64, 16392)])
+def test_matvec_small(q, k, m, n):
+    w = workload(k, m, n)
+    inp = synth.make_inputs(w)
+    ref = oracle.matmat_dense(ref_weights(w, inp), inp.X)
+    got = run_matmat(q, w, inp, use_matvec=True, scale=False)
+    err = rel_err(got, ref)
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    assert np.array_equal(run_matmat(q, w, inp, use_matvec=True, scale=False), got)  # fixed summation order
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+@pytest.mark.parametrize("B", [1, 2, 5, 16, 31, 32, 33, 64, 65, 130])
+def test_matmat_small_with_row_scale(q, k, B):
+    m, n = 96, 1112
+    w = workload(k, m, n, B=B, row_scale=True, sub=B)
+    inp = synth.make_inputs(w)
+    Wref = ref_weights(w, inp)
+    ref = oracle.matmat_dense(Wref, inp.X, inp.row_scale)
+    got = run_matmat(q, w, inp)
+    err = rel_err(got, ref)
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    assert rel_err(run_matmat(q, w, inp, scale=False), oracle.matmat_dense(Wref, inp.X)) <= OBSERVED_TOL
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+@pytest.mark.parametrize("m,n,B", [(288, 1112, 16), (1056, 8, 7), (32, 4104, 40), (64, 8, 96)])
+def test_matmat_ragged_shapes(q, k, m, n, B):
+    """Waves with no blocks at all (n = 8), odd block counts per wave, ragged batch tails."""
+    w = workload(k, m, n, B=B, row_scale=True, sub=B + 1)
+    inp = synth.make_inputs(w)
+    ref = oracle.matmat_dense(ref_weights(w, inp), inp.X, inp.row_scale)
+    err = rel_err(run_matmat(q, w, inp), ref)
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+
+
+def test_layer_call_equals_the_two_calls(q):
+    import torch
+    w = workload(2, 64, 2048, row_scale=True, sub=3)
+    inp = synth.make_inputs(w)
+    rng = np.random.default_rng(77)
+    signs = rng.choice(np.array([-1, 1], dtype=np.int8), w.n)
+    codes, lut, X, sc, sg = dev(inp.codes), dev(inp.lut), dev(inp.X), dev(inp.row_scale), dev(signs)
+    xt = torch.empty((1, w.n), dtype=torch.float16, device="cuda")
+    q.qtip_rht(X, sg, w.n, 512, 1, 0, xt)
+    y2 = torch.empty((1, w.m), dtype=torch.float32, device="cuda")
+    q.qtip_decode_matmat(codes, 14, 2, 1, CODE_LUT, lut, w.m, w.n, xt, 1, sc, y2)
+    y1 = torch.full((w.m,), float("nan"), dtype=torch.float32, device="cuda")
+    scratch = torch.empty(w.n, dtype=torch.float16, device="cuda")
+    q.qtip_rht_decode_matvec(codes, 14, 2, 1, CODE_LUT, lut, w.m, w.n, X, sg, 512, sc, y1, scratch)
+    torch.cuda.synchronize()
+    assert np.array_equal(y1.cpu().numpy(), y2.cpu().numpy()[0])
+    with pytest.raises(q.QtipError):  # this code always takes two launches
+        q.qtip_rht_decode_matvec(codes, 14, 2, 1, CODE_LUT, lut, w.m, w.n, X, sg, 512, sc, y1, None)
+
+
+def test_full_size(q):
+    """The 2-bit 8192 x 28672 shape in the launch configuration the benchmark times: sampled
+    rows of the decoded matrix and sampled outputs, each computed alone by the oracle."""
+    w = synth.WORKLOADS["next_lut14_k2_8192x28672"]
+    inp = synth.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 7)
+    I = int(rng.integers(0, w.m // 32))
+    rows = sorted(set(range(32 * I, 32 * I + 32)) | {0, w.m - 1} | set(int(r) for r in rng.integers(0, w.m, 32)))
+    rows = np.array(rows, dtype=np.int32)
+    got_W = run_dequantize(q, w, inp)
+    for i in rows[::4]:
+        ref_row = np.array([oracle.decode_element(inp.codes, 14, w.k, 1, CODE_LUT, w.n, int(i), j, inp.lut,
+                                                  tile=TILE) for j in range(0, w.n, 7)], dtype=np.uint16)
+        assert np.array_equal(got_W[i, ::7], ref_row)
+    del got_W
+    ref = oracle.decode_matmat_rows(inp.codes, 14, w.k, 1, CODE_LUT, w.m, w.n, inp.X, rows, inp.lut, tile=TILE)
+    got = run_matmat(q, w, inp)
+    assert np.all(np.isfinite(got))
+    err = float(np.abs(got[:, rows] - ref).max() / np.abs(ref).max())
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    # batched, on the matrix cores, same shape
+    w16 = synth.Workload("lut14_b16", 7, 1, w.m, w.n, CODE_LUT, 2, 1, 4096, 4096, B=16, L=14)
+    inp16 = synth.make_inputs(w16)
+    ref = oracle.decode_matmat_rows(inp16.codes, 14, 2, 1, CODE_LUT, w.m, w.n, inp16.X, rows[:20], inp16.lut,
+                                    tile=TILE)
+    got = run_matmat(q, w16, inp16)
+    err = float(np.abs(got[:, rows[:20]] - ref).max() / np.abs(ref).max())
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+
+
+def test_error_codes(q):
+    import torch
+    w = workload(2, 32, 64)
+    inp = synth.make_inputs(w)
+    codes, lut, X = dev(inp.codes), dev(inp.lut), dev(inp.X)
+    Y = torch.empty((1, 32), dtype=torch.float32, device="cuda")
+    with pytest.raises(q.QtipError, match="L = 16"):
+        q.qtip_decode_matvec(codes, 16, 2, 1, CODE_LUT, lut, 32, 64, X, Y)
+    with pytest.raises(q.QtipError, match="lut"):
+        q.qtip_decode_matvec(codes, 14, 2, 1, CODE_LUT, None, 32, 64, X, Y)
+    with pytest.raises(q.QtipError, match="multiple of 32"):
+        q.qtip_decode_matvec(codes, 14, 2, 1, CODE_LUT, lut, 16, 64, X, Y)
+    with pytest.raises(q.QtipError, match="V = 2"):
+        q.qtip_decode_matvec(codes, 14, 2, 2, CODE_LUT, lut, 32, 64, X, Y)
+    with pytest.raises(q.QtipError, match="L = 14"):
+        q.qtip_decode_matvec(codes, 14, 2, 1, synth.CODE_3INST, None, 32, 64, X, Y)
