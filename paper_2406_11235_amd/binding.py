@@ -163,8 +163,8 @@ def qtip_quantize(W, m, n, L, k, V, code_id, lut=None):
     assert W.shape == (m, n)
     if lut is not None:
         lut = np.ascontiguousarray(lut)
-        assert lut.dtype in (np.float16, np.uint16) and lut.size == 1024
-    codes = np.zeros(((m // 16) * (n // 16), 8 * k), dtype=np.uint32)
+        assert lut.dtype in (np.float16, np.uint16) and lut.size == (1 << 14 if code_id == CODE_LUT else 1024)
+    codes = np.zeros((m * n // 256, 8 * k), dtype=np.uint32)  # one sequence per 256 weights
     mse = ctypes.c_double(0.0)
     _check(lib().qtip_quantize(_ptr(W), m, n, L, k, V, code_id, _ptr(lut), _ptr(codes),
                                ctypes.addressof(mse)))

@@ -187,10 +187,9 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
     const char *fn = "qtip_quantize";
     if (!W || !codes_out) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
-    if (is_lut(code_id)) return fail(QTIP_EUNSUPPORTED, "%s: the lookup-only code is not built here", fn);
     int rc;
     try {
-        rc = qtip::quantize_host(W, m, n, k, V, code_id, (const uint16_t *)lut_f16, codes_out, mse_out);
+        rc = qtip::quantize_host(W, m, n, L, k, V, code_id, (const uint16_t *)lut_f16, codes_out, mse_out);
     } catch (const std::bad_alloc &) {
         return fail(QTIP_ENOMEM, "%s: out of host memory", fn);
     } catch (...) {
@@ -211,7 +210,6 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
     const char *fn = "qtip_quantize_gpu";
     if (!W || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
-    if (is_lut(code_id)) return fail(QTIP_EUNSUPPORTED, "%s: the lookup-only code is not built here", fn);
     if (((uintptr_t)W | (uintptr_t)codes_out | (uintptr_t)tile_err) % 4 || (uintptr_t)workspace % 256)
         return fail(QTIP_EINVAL, "%s: W, codes_out, tile_err need 4-byte, workspace 256-byte alignment", fn);
     if (workspace_bytes < qtip::quantize_gpu_workspace(k, V, 1))

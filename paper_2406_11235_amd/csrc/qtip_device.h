@@ -33,6 +33,9 @@ constexpr int CODE_3INST = 1;
 constexpr int CODE_HYB = 2;
 constexpr int CODE_HYB2 = 3;  // HYB with a second sign flip (bit 31 of the hash on the first entry)
 constexpr int CODE_LUT = 4;   // lookup-only: L = 14, V = 1, 32 x 8 blocks (kernels in qtip_lut14.hip)
+// state bits L and log2 of T_y (a sequence is a (256 / T_y) x T_y block of the matrix)
+__host__ __device__ constexpr int code_state_bits(int code) { return code == CODE_LUT ? 14 : 16; }
+__host__ __device__ constexpr int code_log2_ty(int code) { return code == CODE_LUT ? 3 : 4; }
 __host__ __device__ constexpr bool code_is_hyb(int code) { return code == CODE_HYB || code == CODE_HYB2; }
 
 // Section 3.1.1 constants.

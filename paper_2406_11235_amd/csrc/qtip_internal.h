@@ -33,7 +33,7 @@ hipError_t launch_lut_decode_states(const uint32_t *states, int count, const voi
                                     hipStream_t st);
 
 // Host-only tail-biting Viterbi quantizer (qtip_quantize.cpp).
-int quantize_host(const float *W, int m, int n, int k, int V, int code_id, const uint16_t *lut,
+int quantize_host(const float *W, int m, int n, int L, int k, int V, int code_id, const uint16_t *lut,
                   uint32_t *codes_out, double *mse_out);
 
 // GPU tail-biting Viterbi quantizer (qtip_viterbi.hip).  W is m x n with row stride ld

@@ -1,6 +1,8 @@
-// Host-only quantizer behind qtip_quantize: Viterbi on the (16, k, V) bitshift
+// Host-only quantizer behind qtip_quantize: Viterbi on the (L, k, V) bitshift
 // trellis (Section 2.3 of arXiv 2406.11235) with the tail-biting approximation of
-// Algorithm 4, one 16x16 tile = one length-256 sequence (Section 4).  It exists to
+// Algorithm 4, one T_x x T_y block = one length-256 sequence (Section 4): L = 16 and
+// 16 x 16 blocks for the codes of Algorithms 1-3, L = 14 and 32 x 8 blocks for the
+// lookup-only code.  It exists to
 // produce valid code streams for tests and examples; it is never on a timed path.
 //
 // The dynamic program is arranged around the trellis' structure: every state y
@@ -20,8 +22,6 @@
 namespace qtip {
 namespace {
 
-constexpr int L = 16;
-constexpr int NS = 1 << L;
 constexpr int T = 256;
 
 float half_bits_to_float(uint16_t h) {
@@ -30,11 +30,14 @@ float half_bits_to_float(uint16_t h) {
     return (float)v;
 }
 
-// The three codes on the host (Algorithms 1-3), values as float.
-void build_codebook(int V, int code_id, const uint16_t *lut, std::vector<float> &C) {
+// The codes on the host (Algorithms 1-3; code 4: a stored table), values as float.
+void build_codebook(int L, int V, int code_id, const uint16_t *lut, std::vector<float> &C) {
+    const int NS = 1 << L;
     C.resize((size_t)NS * V);
     for (uint32_t x = 0; x < (uint32_t)NS; x++) {
-        if (code_id == 0) {
+        if (code_id == 4) {
+            C[x] = half_bits_to_float(lut[x]);
+        } else if (code_id == 0) {
             uint32_t X = x * 34038481u + 76625530u;
             int s = (int)(X & 255u) + (int)((X >> 8) & 255u) + (int)((X >> 16) & 255u) + (int)(X >> 24);
             C[x] = (float)(_Float16)((double)(s - 510) / 147.8);
@@ -63,9 +66,9 @@ struct Workspace {
 };
 
 // One Viterbi pass over `S` (T values).  first_top / last_low < 0 = unconstrained.
-double viterbi(const float *S, int k, int V, const float *C, int first_top, int last_low,
+double viterbi(const float *S, int L, int k, int V, const float *C, int first_top, int last_low,
                Workspace &ws) {
-    const int kV = k * V, ov = L - kV, G = T / V;
+    const int kV = k * V, ov = L - kV, G = T / V, NS = 1 << L;
     const int NP = 1 << ov, NC = 1 << kV;
     const double INF = std::numeric_limits<double>::infinity();
     ws.val.assign(NS, 0.0);
@@ -120,14 +123,14 @@ double viterbi(const float *S, int k, int V, const float *C, int first_top, int 
 }
 
 // Algorithm 4 on one sequence; writes 8k words, returns the squared error.
-double quantize_sequence(const float *S, int k, int V, const float *C, uint32_t *words,
+double quantize_sequence(const float *S, int L, int k, int V, const float *C, uint32_t *words,
                          Workspace &ws) {
     const int kV = k * V, ov = L - kV, G = T / V;
     float Sr[T];
     for (int i = 0; i < T; i++) Sr[(i + T / 2) % T] = S[i];
-    viterbi(Sr, k, V, C, -1, -1, ws);
+    viterbi(Sr, L, k, V, C, -1, -1, ws);
     const int O = (int)(ws.states[(T / 2) / V - 1] & ((1u << ov) - 1u));
-    const double d = viterbi(S, k, V, C, O, O, ws);
+    const double d = viterbi(S, L, k, V, C, O, O, ws);
     std::memset(words, 0, sizeof(uint32_t) * 8 * k);
     for (int t = 0; t < G; t++) {
         const uint32_t top = ws.states[t] >> ov;  // the kV new bits of this step
@@ -141,11 +144,12 @@ double quantize_sequence(const float *S, int k, int V, const float *C, uint32_t 
 
 }  // namespace
 
-int quantize_host(const float *W, int m, int n, int k, int V, int code_id, const uint16_t *lut,
+int quantize_host(const float *W, int m, int n, int L, int k, int V, int code_id, const uint16_t *lut,
                   uint32_t *codes_out, double *mse_out) {
     std::vector<float> C;
-    build_codebook(V, code_id, lut, C);
-    const int tm = m / 16, tn = n / 16;
+    build_codebook(L, V, code_id, lut, C);
+    const int tx = code_id == 4 ? 32 : 16, ty = T / tx;  // the block that is one sequence
+    const int tm = m / tx, tn = n / ty;
     const long ntiles = (long)tm * tn;
     unsigned nthreads = std::thread::hardware_concurrency();
     if (nthreads == 0) nthreads = 1;
@@ -162,8 +166,8 @@ int quantize_host(const float *W, int m, int n, int k, int V, int code_id, const
                 if (tile >= ntiles) break;
                 const long I = tile / tn, J = tile % tn;
                 for (int s = 0; s < T; s++)
-                    S[s] = W[(size_t)(16 * I + s / 16) * n + (16 * J + s % 16)];
-                err[id] += quantize_sequence(S, k, V, C.data(), codes_out + (size_t)tile * 8 * k, ws);
+                    S[s] = W[(size_t)(tx * I + s / ty) * n + (ty * J + s % ty)];
+                err[id] += quantize_sequence(S, L, k, V, C.data(), codes_out + (size_t)tile * 8 * k, ws);
             }
         } catch (...) {
             failed = true;

@@ -1,7 +1,8 @@
-// GPU quantizer: the Viterbi algorithm on the (16, k, V) bitshift trellis (Section 2.3 of
+// GPU quantizer: the Viterbi algorithm on the (L, k, V) bitshift trellis (Section 2.3 of
 // arXiv 2406.11235: value function and update rule; Section 3.1: edge rule), made
-// tail-biting by Algorithm 4, one 16x16 tile = one length-256 sequence (Section 4), for
-// the computed codes of Algorithms 1-3.
+// tail-biting by Algorithm 4, one T_x x T_y block = one length-256 sequence (Section 4), for
+// the computed codes of Algorithms 1-3 (L = 16, 16 x 16 blocks) and the lookup-only code of
+// the appendix (L = 14, 32 x 8 blocks; the text below says 16 and 1024, read L and 2^L / 64).
 //
 // Layout on the chip.  One workgroup of NT = 1024 threads owns one sequence and keeps the
 // whole value function, 2^16 binary32 numbers, in registers: thread `tid` holds the 64
@@ -42,31 +43,30 @@
 namespace qtip {
 namespace {
 
-constexpr int VT_T = 256;           // sequence length (one 16x16 tile)
-#ifndef QTIP_VITERBI_THREADS
-#define QTIP_VITERBI_THREADS 1024
-#endif
-constexpr int VT_NT = QTIP_VITERBI_THREADS;  // threads per sequence
-constexpr int VT_REGS = 65536 / VT_NT;        // states per thread
+constexpr int VT_T = 256;    // sequence length (one T_x x T_y block)
+constexpr int VT_REGS = 64;  // states per thread
 
-template <int KV>
+// LB = L, the number of state bits: 16 (NT = 1024 threads per sequence) for the codes of
+// Algorithms 1-3, 14 (NT = 256) for the lookup-only code.
+template <int KV, int LB>
 struct VitGeo {
-    static constexpr int OV = 16 - KV;              // bits two consecutive states share
+    static constexpr int NT = (1 << LB) / VT_REGS;  // threads per sequence
+    static constexpr int OV = LB - KV;              // bits two consecutive states share
     static constexpr int NP = 1 << OV;              // prefixes = minima per step
     static constexpr int NC = 1 << KV;              // predecessors per prefix
-    static constexpr bool LOCAL = NP >= VT_NT;      // predecessors of a prefix in one thread
-    static constexpr int NB1 = LOCAL ? NP / VT_NT : 1;  // prefixes per thread
+    static constexpr bool LOCAL = NP >= NT;         // predecessors of a prefix in one thread
+    static constexpr int NB1 = LOCAL ? NP / NT : 1;     // prefixes per thread
     // back-pointers: kV bits per prefix, FPW whole fields per word, PWT words per thread
     static constexpr int FPW = 32 / KV;
     static constexpr int PWT = (NB1 + FPW - 1) / FPW;
-    // kV <= 3: a thread can own, for a few values "mid" of the middle 16 - 2 kV bits of the
+    // kV <= 3: a thread can own, for a few values "mid" of the middle L - 2 kV bits of the
     // state, all 2^kV x 2^kV states (p, mid, c).  Then the predecessors of a prefix (mid, c)
     // are still its own registers, and so are all 2^kV children of a prefix it reads back, so
     // one LDS read serves 2^kV states and a thread's minima are contiguous in LDS (16-byte
     // LDS operations).  SJ = mids per thread: mid = SJ tid + j.
-    static constexpr bool SLOT = VT_NT == 1024 && KV <= 3;
+    static constexpr bool SLOT = KV <= 3;
     static constexpr int SJ = SLOT ? VT_REGS / (NC * NC) : 1;
-    static constexpr int PW = SLOT ? VT_NT : LOCAL ? VT_NT * PWT : NP;  // back-pointer words per step
+    static constexpr int PW = SLOT ? NT : LOCAL ? NT * PWT : NP;  // back-pointer words per step
 };
 
 __host__ __device__ constexpr int vit_max(int a, int b) { return a > b ? a : b; }
@@ -108,12 +108,14 @@ __device__ __forceinline__ void argmin_regs(const float (&val)[VT_REGS], int bas
 // the first state's top 16-kV bits and the last state's low 16-kV bits are forced to
 // overlap[slot] (its second call).  Sequence `slot` of the batch is tile tile0 + slot.
 template <int KV, int V, int CODE>
-__global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
+// (four waves per SIMD, i.e. at most 128 registers, also where a workgroup is only four waves)
+__global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void viterbi_forward_kernel(
     const float *__restrict__ W, int n, int tn, long tile0, const uint32_t *__restrict__ lut, int rotate,
     const uint32_t *__restrict__ overlap, uint32_t *__restrict__ ptrs, uint32_t *__restrict__ final_state,
     float *__restrict__ final_value) {
-    using Geo = VitGeo<KV>;
-    constexpr int NP = Geo::NP, NC = Geo::NC, NB1 = Geo::NB1, PW = Geo::PW;
+    using Geo = VitGeo<KV, code_state_bits(CODE)>;
+    constexpr int NP = Geo::NP, NC = Geo::NC, NB1 = Geo::NB1, PW = Geo::PW, VT_NT = Geo::NT;
+    constexpr int LTY = code_log2_ty(CODE), TY = 1 << LTY, TX = VT_T >> LTY;  // the block is TX x TY
     constexpr int G = VT_T / V;
     constexpr bool HYB = code_is_hyb(CODE);
     constexpr int ROWS = CODE == CODE_HYB2 ? 2048 : 1024;  // signed table rows a state can select
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
     static_assert(VT_NT >= VT_T, "one thread per sequence element");
     if (tid < VT_T) {
         const int s = rotate ? ((tid + VT_T / 2) & (VT_T - 1)) : tid;
-        s_seq[tid] = W[(size_t)(16 * I + (s >> 4)) * n + 16 * J + (s & 15)];
+        s_seq[tid] = W[(size_t)(TX * I + (s >> LTY)) * n + TY * J + (s & (TY - 1))];
     }
     __syncthreads();
     auto seq = [&](int u) -> float { return s_seq[u]; };
@@ -165,7 +167,10 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
             else
                 ipk[r >> 1] = row * 4;
         } else {
-            cpk[r >> 1][r & 1] = CODE == CODE_3INST ? code_3inst(y) : code_1mad(y);
+            if constexpr (CODE == CODE_LUT)
+                cpk[r >> 1][r & 1] = reinterpret_cast<const half_t *>(lut)[y];
+            else
+                cpk[r >> 1][r & 1] = CODE == CODE_3INST ? code_3inst(y) : code_1mad(y);
         }
     }
     // (opaque to the compiler from here on, or it recomputes the codes inside the loop
@@ -398,13 +403,13 @@ __global__ __launch_bounds__(VT_NT) void viterbi_forward_kernel(
 // pass 1: down to step G/2 - 1, whose low 16-kV bits are the overlap of Algorithm 4.
 // pass 2: the whole walk; step t contributes the top kV bits of its state as stream bits
 // t kV .. (t+1) kV - 1 (first bit = most significant bit of word 0).
-template <int KV, int V>
+template <int KV, int V, int LB>
 __global__ __launch_bounds__(64) void viterbi_backtrace_kernel(
     const uint32_t *__restrict__ ptrs, const uint32_t *__restrict__ final_state,
     const float *__restrict__ final_value, int count, int pass, uint32_t *__restrict__ overlap,
     uint32_t *__restrict__ codes, float *__restrict__ tile_err, long tile0) {
-    using Geo = VitGeo<KV>;
-    constexpr int OV = Geo::OV, NP = Geo::NP, NC = Geo::NC, PW = Geo::PW;
+    using Geo = VitGeo<KV, LB>;
+    constexpr int OV = Geo::OV, NP = Geo::NP, NC = Geo::NC, PW = Geo::PW, VT_NT = Geo::NT;
     constexpr int G = VT_T / V, NWORDS = KV * G / 32;
     const int slot = blockIdx.x * blockDim.x + threadIdx.x;
     if (slot >= count) return;
@@ -450,9 +455,9 @@ __global__ __launch_bounds__(64) void viterbi_backtrace_kernel(
 
 // Workspace for `tiles` sequences in flight: three words per sequence (final state,
 // overlap, final value), then the back-pointers.
-template <int KV, int V>
+template <int KV, int V, int LB>
 constexpr size_t per_tile_bytes() {
-    return (size_t)(VT_T / V) * VitGeo<KV>::PW * sizeof(uint32_t);
+    return (size_t)(VT_T / V) * VitGeo<KV, LB>::PW * sizeof(uint32_t);
 }
 constexpr size_t VT_HEAD_ALIGN = 256;
 
@@ -464,12 +469,14 @@ size_t head_bytes(long tiles) {
 template <int KV, int V, int CODE>
 hipError_t quantize_gpu_t(const float *W, int m, int n, int ld, const uint32_t *lut, uint32_t *codes,
                           float *tile_err, void *ws, size_t ws_bytes, hipStream_t st) {
-    const int tn = n / 16;
-    const long ntiles = (long)(m / 16) * tn;
+    constexpr int LB = code_state_bits(CODE), VT_NT = VitGeo<KV, LB>::NT;
+    constexpr int TY = 1 << code_log2_ty(CODE), TX = VT_T / TY;
+    const int tn = n / TY;
+    const long ntiles = (long)(m / TX) * tn;
     // the largest batch the workspace holds
-    long cap = (long)(ws_bytes / per_tile_bytes<KV, V>());  // upper bound, trimmed below
+    long cap = (long)(ws_bytes / per_tile_bytes<KV, V, LB>());  // upper bound, trimmed below
     if (cap > ntiles) cap = ntiles;
-    while (cap > 0 && head_bytes(cap) + (size_t)cap * per_tile_bytes<KV, V>() > ws_bytes) cap--;
+    while (cap > 0 && head_bytes(cap) + (size_t)cap * per_tile_bytes<KV, V, LB>() > ws_bytes) cap--;
     if (cap <= 0) return hipErrorInvalidValue;
     uint32_t *final_state = (uint32_t *)ws;
     uint32_t *overlap = final_state + cap;
@@ -480,11 +487,11 @@ hipError_t quantize_gpu_t(const float *W, int m, int n, int ld, const uint32_t *
         const dim3 bgrid((cnt + 63) / 64);
         hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, ld, tn,
                            tile0, lut, 1, (const uint32_t *)nullptr, ptrs, final_state, final_value);
-        hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V>), bgrid, dim3(64), 0, st, ptrs, final_state,
+        hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V, LB>), bgrid, dim3(64), 0, st, ptrs, final_state,
                            final_value, cnt, 1, overlap, codes, tile_err, tile0);
         hipLaunchKernelGGL((viterbi_forward_kernel<KV, V, CODE>), dim3(cnt), dim3(VT_NT), 0, st, W, ld, tn,
                            tile0, lut, 0, (const uint32_t *)overlap, ptrs, final_state, final_value);
-        hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V>), bgrid, dim3(64), 0, st, ptrs, final_state,
+        hipLaunchKernelGGL((viterbi_backtrace_kernel<KV, V, LB>), bgrid, dim3(64), 0, st, ptrs, final_state,
                            final_value, cnt, 2, overlap, codes, tile_err, tile0);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -498,11 +505,12 @@ size_t quantize_gpu_workspace(int k, int V, long tiles) {
     const int kV = k * V;
     size_t pw;
     switch (kV) {
-        case 2: pw = VitGeo<2>::PW; break;
-        case 3: pw = VitGeo<3>::PW; break;
-        case 4: pw = VitGeo<4>::PW; break;
-        case 6: pw = VitGeo<6>::PW; break;
-        default: pw = VitGeo<8>::PW; break;
+        // (sized for L = 16; the lookup-only code, L = 14, needs a quarter of it)
+        case 2: pw = VitGeo<2, 16>::PW; break;
+        case 3: pw = VitGeo<3, 16>::PW; break;
+        case 4: pw = VitGeo<4, 16>::PW; break;
+        case 6: pw = VitGeo<6, 16>::PW; break;
+        default: pw = VitGeo<8, 16>::PW; break;
     }
     return head_bytes(tiles) + (size_t)tiles * (VT_T / V) * pw * sizeof(uint32_t);
 }
@@ -510,7 +518,11 @@ size_t quantize_gpu_workspace(int k, int V, long tiles) {
 hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, int ld, const uint32_t *lut,
                                uint32_t *codes, float *tile_err, void *ws, size_t ws_bytes,
                                hipStream_t st) {
-    if (code_id == CODE_HYB2) {
+    if (code_id == CODE_LUT) {
+        if (k == 2) return quantize_gpu_t<2, 1, CODE_LUT>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<3, 1, CODE_LUT>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<4, 1, CODE_LUT>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+    } else if (code_id == CODE_HYB2) {
         if (k == 2) return quantize_gpu_t<4, 2, CODE_HYB2>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
         if (k == 3) return quantize_gpu_t<6, 2, CODE_HYB2>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
         return quantize_gpu_t<8, 2, CODE_HYB2>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);

@@ -206,3 +206,70 @@ def test_error_codes(q):
         q.qtip_decode_matvec(codes, 14, 2, 2, CODE_LUT, lut, 32, 64, X, Y)
     with pytest.raises(q.QtipError, match="L = 14"):
         q.qtip_decode_matvec(codes, 14, 2, 1, synth.CODE_3INST, None, 32, 64, X, Y)
+
+
+# ------------------------------------------------------------------ quantizer
+
+def run_quantize_gpu(q, W, k, lut, tiles_in_flight=None):
+    import torch
+    m, n = W.shape
+    ntiles = (m // 32) * (n // 8)
+    ws_bytes = q.qtip_quantize_gpu_workspace(k, 1, tiles_in_flight or ntiles)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    codes = torch.full((ntiles, 8 * k), -1, dtype=torch.int32, device="cuda")
+    err = torch.full((ntiles,), float("nan"), dtype=torch.float32, device="cuda")
+    q.qtip_quantize_gpu(dev(np.ascontiguousarray(W, dtype=np.float32)), m, n, 14, k, 1, CODE_LUT, dev(lut), codes,
+                        err, ws, ws_bytes)
+    torch.cuda.synchronize()
+    return codes.cpu().numpy().view(np.uint32), err.cpu().numpy()
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_quantizer_streams_equal_the_binary32_oracle(q, k):
+    """The search runs in binary32 with a fixed operation order, which the oracle repeats
+    decision by decision (Section 2.3, Algorithm 4): streams and final values bit for bit."""
+    rng = np.random.default_rng(1400 + k)
+    lut = rng.standard_normal(1 << 14).astype(np.float16)
+    C = oracle.codebook(14, 1, CODE_LUT, lut)
+    m, n = 64, 16
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    codes, err = run_quantize_gpu(q, W, k, lut)
+    for I in range(m // 32):
+        for J in range(n // 8):
+            S = W[32 * I:32 * I + 32, 8 * J:8 * J + 8].reshape(-1)
+            d, words = oracle.tailbiting_quantize_f32(S, 14, k, 1, C)
+            assert np.array_equal(codes[I * (n // 8) + J], words), (I, J)
+            assert err[I * (n // 8) + J] == d
+
+
+def test_quantizer_roundtrip_and_distortion(q):
+    """Weights that are decodable come back exactly; on Gaussian input every block's reported
+    error is the binary64 distortion of its own stream, and the mean squared error agrees with
+    the binary64 host search (equally good streams may differ, the distortion may not by more
+    than binary32 rounding)."""
+    rng = np.random.default_rng(1414)
+    lut = rng.standard_normal(1 << 14).astype(np.float16)
+    C = oracle.codebook(14, 1, CODE_LUT, lut)
+    m, n, k = 64, 24, 2
+    codes = rng.integers(0, 1 << 32, ((m // 32) * (n // 8), 8 * k), dtype=np.uint64).astype(np.uint32)
+    W = oracle.dequantize(codes, 14, k, 1, CODE_LUT, m, n, lut, tile=TILE).view(np.float16).astype(np.float32)
+    codes2, err = run_quantize_gpu(q, W, k, lut)
+    assert np.all(err == 0.0)
+    W2 = oracle.dequantize(codes2, 14, k, 1, CODE_LUT, m, n, lut, tile=TILE).view(np.float16).astype(np.float32)
+    assert np.array_equal(W, W2)
+    m, n = 128, 64   # 32 blocks, two batches of 20 and 12
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    codes, err = run_quantize_gpu(q, W, k, lut, tiles_in_flight=20)
+    tot = 0.0
+    for I in range(m // 32):
+        for J in range(n // 8):
+            S = W[32 * I:32 * I + 32, 8 * J:8 * J + 8].reshape(-1).astype(np.float64)
+            d = oracle.stream_distortion(codes[I * (n // 8) + J], S, 14, k, 1, C)
+            assert abs(err[I * (n // 8) + J] - d) <= 1e-4 * d
+            tot += d
+    mse = tot / (m * n)
+    _, mse_host = q.qtip_quantize(W, m, n, 14, k, 1, CODE_LUT, lut)
+    assert abs(mse - mse_host) <= 2e-3 * mse_host, (mse, mse_host)
+    # between Table 1's L = 16 random-table entry (0.068) and Table 2's L = 12 entry (0.0733), give or
+    # take the noise of 8192 samples
+    assert 0.066 < mse < 0.076, mse

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2
+from oracle import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT
 
 
 @pytest.fixture(scope="module")
@@ -37,6 +37,27 @@ def test_quantizer_matches_oracle_algorithm4(q, code_id, k, V):
         tot += d
         # equally good streams may differ in bits; the distortion may not
         assert abs(oracle.stream_distortion(codes[J], S, 16, k, V, C) - d) < 1e-6 * max(d, 1)
+    assert abs(tot / (m * n) - mse) < 1e-6 * max(mse, 1e-3)
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_lookup_only_code_matches_oracle_algorithm4(q, k):
+    """L = 14, 32 x 8 blocks: the block that is one sequence and the table lookup."""
+    rng = np.random.default_rng(140 + k)
+    lut = rng.standard_normal(1 << 14).astype(np.float16)
+    C = oracle.codebook(14, 1, CODE_LUT, lut)
+    m, n = 32, 16
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    codes, mse = q.qtip_quantize(W, m, n, 14, k, 1, CODE_LUT, lut)
+    assert codes.shape == (2, 8 * k)
+    Wd = oracle.dequantize(codes, 14, k, 1, CODE_LUT, m, n, lut, tile=(32, 8)).view(np.float16).astype(np.float64)
+    assert abs(((Wd - W) ** 2).mean() - mse) < 1e-9
+    tot = 0.0
+    for J in range(2):
+        S = W[:, 8 * J:8 * J + 8].reshape(-1).astype(np.float64)
+        d, words = oracle.tailbiting_quantize(S, 14, k, 1, C)
+        tot += d
+        assert abs(oracle.stream_distortion(codes[J], S, 14, k, 1, C) - d) < 1e-6 * max(d, 1)
     assert abs(tot / (m * n) - mse) < 1e-6 * max(mse, 1e-3)
 
 
