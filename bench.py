@@ -306,21 +306,30 @@ def main():
                 "frac": lane_ops / (r["ms_hot"] * 1e-3) / peak,
                 "valu_wave_instructions_per_launch": MEASURED_VALU_WAVE_INSTS[w.name]}
 
+    # The lookup-only code is bound by its table reads: one 2-byte LDS read per weight at random
+    # addresses.  Peak: 32 four-byte banks per CU, each serving one address per cycle.
+    lds = None
+    if w.code_id == synth.CODE_LUT:
+        lookups = w.m * w.n
+        peak = 256 * 32 * 2.4e9
+        lds = {"bound": "lds", "kernel": "decode+matvec", "unit": "T table reads/s",
+               "achieved": lookups / (r["ms_hot"] * 1e-3) / 1e12, "peak": peak / 1e12,
+               "frac": lookups / (r["ms_hot"] * 1e-3) / peak, "table_reads_per_launch": lookups}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
         rows = 2048
-        tn = w.n // 16
-        slab = st["inp"].codes[: (rows // 16) * tn]
+        slab = st["inp"].codes[: (rows // w.tile[0]) * (w.n // w.tile[1])]
         xt = st["xt"].cpu().numpy()
         t0 = time.perf_counter()
-        Wd = oracle.dequantize(slab, w.L, w.k, w.V, w.code_id, rows, w.n, st["inp"].lut)
+        Wd = oracle.dequantize(slab, w.L, w.k, w.V, w.code_id, rows, w.n, st["inp"].lut, tile=w.tile)
         yref = oracle.matmat_dense(Wd, xt)
         dt = time.perf_counter() - t0
         reps = 1
         while dt < 10.0 and reps < 64:          # extend to about 10 s of CPU work
             t1 = time.perf_counter()
-            Wd = oracle.dequantize(slab, w.L, w.k, w.V, w.code_id, rows, w.n, st["inp"].lut)
+            Wd = oracle.dequantize(slab, w.L, w.k, w.V, w.code_id, rows, w.n, st["inp"].lut, tile=w.tile)
             yref = oracle.matmat_dense(Wd, xt)
             dt += time.perf_counter() - t1
             reps += 1
@@ -362,7 +371,7 @@ def main():
 
     out = {
         "metric": "batch-1 decode+matvec effective HBM GB/s on compressed-weight bytes, "
-                  "2-bit 3INST 8192x28672",
+                  + ("2-bit 3INST 8192x28672" if w.name == WORKLOAD else w.name),
         "value": gbs(r["ms_step"]), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": r["ms_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
@@ -373,7 +382,7 @@ def main():
         "us_per_matvec": r["ms_kernel"] * 1e3, "us_rht": r["ms_rht"] * 1e3,
         "ms_per_step_hipgraph": r["ms_step_graph"],
         "pct_of_hbm_peak": gbs(r["ms_kernel"]) / HBM_PEAK_GBS * 100,
-        "roofline": roofline, "roofline_alu": valu, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "roofline_alu": valu, "roofline_lds": lds, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out), flush=True)
 
