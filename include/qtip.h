@@ -192,24 +192,26 @@ int qtip_quantize_gpu(const float *W, int m, int n, int L, int k, int V, int cod
 
 /*
  * Block LDL decomposition of a proxy Hessian (Algorithm 5, second and third lines, with
- * T_y = 16): H = L D L^T, L unit block lower triangular with 16x16 identity blocks on
- * its diagonal, D block diagonal; the feedback matrix is A = L - I.
+ * T_y = g): H = L D L^T, L unit block lower triangular with g x g identity blocks on
+ * its diagonal, D block diagonal; the feedback matrix is A = L - I.  g is 16 (the codes of
+ * Algorithms 1-3) or 8 (the lookup-only code); n a multiple of 16.
  *   H:       device, n x n row-major binary64, symmetric positive definite (only its
  *            lower triangle is read).  If it is not positive definite the results
  *            hold non-finite values; no error is raised.
  *   A_out:   device, n x n row-major fp32: L - I (zero on and above the diagonal blocks).
- *   D_out:   device, (n/16) x 16 x 16 binary64, or NULL: the diagonal blocks of D.
+ *   D_out:   device, (n/g) x g x g binary64, or NULL: the diagonal blocks of D.
  *   workspace: device, 256-byte aligned, qtip_block_ldl_workspace(n) bytes (two n x n
  *            binary64 matrices); contents are scratch.
- * Binary64 throughout; 2 n/16 + 2 kernel launches on `stream`, no synchronization.
+ * Binary64 throughout; 2 n/g + 2 kernel launches on `stream`, no synchronization.
  */
 size_t qtip_block_ldl_workspace(int n);
-int qtip_block_ldl(const double *H, int n, float *A_out, double *D_out, void *workspace,
+int qtip_block_ldl(const double *H, int n, int g, float *A_out, double *D_out, void *workspace,
                    size_t workspace_bytes, void *stream);
 
 /*
- * The quantizer inside BlockLDLQ (Algorithm 5 with T_x = T_y = 16): for column blocks j
- * from the last to the first,
+ * The quantizer inside BlockLDLQ (Algorithm 5; written here for T_x = T_y = 16; with the
+ * lookup-only code read 32 x 8 blocks, column blocks of 8 and A from qtip_block_ldl with
+ * g = 8): for column blocks j from the last to the first,
  *     x = W[:, 16j:16j+16] + (W - What)[:, 16j+16:] A[16j+16:, 16j:16j+16],
  * every 16x16 block of x quantized as one sequence by the tail-biting Viterbi quantizer
  * (as qtip_quantize_gpu, same arithmetic), What[:, 16j:16j+16] = its decode.
@@ -219,7 +221,7 @@ int qtip_block_ldl(const double *H, int n, float *A_out, double *D_out, void *wo
  *   (m/16)*(n/16) floats or NULL: squared error of every tile against its x.
  *   workspace: 256-byte aligned; qtip_quantize_ldlq_workspace(m, n, k, V, t) bytes keep
  *   t tiles of a column block in flight (a block has m/16 tiles; t = m/16 is the most
- *   that helps; any t >= 1 works).
+ *   that helps; any t >= 1 works; the size is computed for 16 x 16 blocks and covers 32 x 8).
  * The feedback sum is binary32, one fused multiply-add per term, column blocks from the last
  * one down and ascending inside a block, so that the input of the quantizer is reproducible.
  * The workspace holds a running m x n fp32 sum besides the quantizer's own.

@@ -361,30 +361,33 @@ def ldlq_feedback_f32(W, E, A, j, g=16):
     return x
 
 
-def ldlq_quantize_f32(W, A, L, k, V, code_id, lut=None, rounder=None):
-    """Algorithm 5 with T_x = T_y = 16: column blocks from the last to the first, feedback in
-    binary32 (ldlq_feedback_f32), every 16x16 block of x rounded as one sequence by the
-    binary32 tail-biting quantizer.  Returns (codes (tiles, 8k), What float32, x of every block).
-    `rounder(S) -> (value, words)` replaces the quantizer (tests)."""
+def ldlq_quantize_f32(W, A, L, k, V, code_id, lut=None, rounder=None, tile=(16, 16)):
+    """Algorithm 5 with tile = (T_x, T_y): column blocks of T_y from the last to the first,
+    feedback in binary32 (ldlq_feedback_f32), every T_x x T_y block of x rounded as one sequence
+    by the binary32 tail-biting quantizer.  Returns (codes (tiles, 8k), What float32, x of every
+    block).  `rounder(S) -> (value, words)` replaces the quantizer (tests)."""
     W, A = _f32(W), _f32(A)
     m, n = W.shape
-    tn = n // 16
+    Tx, Ty = tile
+    assert Tx * Ty == 256
+    tn = n // Ty
     C = codebook(L, V, code_id, lut)
-    codes = np.zeros(((m // 16) * tn, 8 * k), dtype=np.uint32)
+    codes = np.zeros(((m // Tx) * tn, 8 * k), dtype=np.uint32)
     What = np.zeros((m, n), dtype=np.float32)
     E = np.zeros((m, n), dtype=np.float32)
     xs = np.zeros((m, n), dtype=np.float32)
     for j in range(tn - 1, -1, -1):
-        x = ldlq_feedback_f32(W, E, A, j)
-        xs[:, 16 * j:16 * j + 16] = x
-        for I in range(m // 16):
-            S = x[16 * I:16 * I + 16, :].reshape(-1)
+        cols = slice(Ty * j, Ty * j + Ty)
+        x = ldlq_feedback_f32(W, E, A, j, Ty)
+        xs[:, cols] = x
+        for I in range(m // Tx):
+            S = x[Tx * I:Tx * I + Tx, :].reshape(-1)
             if rounder is None:
                 _, words = tailbiting_quantize_f32(S, L, k, V, C)
             else:
                 _, words = rounder(S)
             codes[I * tn + j] = words
             vals, _ = decode_sequence_table(words, 256, L, k, V, C)
-            What[16 * I:16 * I + 16, 16 * j:16 * j + 16] = vals.reshape(16, 16).astype(np.float32)
-        E[:, 16 * j:16 * j + 16] = W[:, 16 * j:16 * j + 16] - What[:, 16 * j:16 * j + 16]
+            What[Tx * I:Tx * I + Tx, cols] = vals.reshape(Tx, Ty).astype(np.float32)
+        E[:, cols] = W[:, cols] - What[:, cols]
     return codes, What, xs

@@ -75,7 +75,7 @@ def lib():
         L.qtip_block_ldl_workspace.restype = c.c_size_t
         L.qtip_block_ldl_workspace.argtypes = [i32]
         L.qtip_block_ldl.restype = i32
-        L.qtip_block_ldl.argtypes = [vp, i32, vp, vp, vp, c.c_size_t, vp]
+        L.qtip_block_ldl.argtypes = [vp, i32, i32, vp, vp, vp, c.c_size_t, vp]
         L.qtip_quantize_ldlq_workspace.restype = c.c_size_t
         L.qtip_quantize_ldlq_workspace.argtypes = [i32, i32, i32, i32, c.c_long]
         L.qtip_quantize_ldlq.restype = i32
@@ -186,8 +186,8 @@ def qtip_block_ldl_workspace(n):
     return int(lib().qtip_block_ldl_workspace(n))
 
 
-def qtip_block_ldl(H, n, A_out, D_out, workspace, workspace_bytes, stream=None):
-    return _check(lib().qtip_block_ldl(_ptr(H), n, _ptr(A_out), _ptr(D_out), _ptr(workspace),
+def qtip_block_ldl(H, n, A_out, D_out, workspace, workspace_bytes, stream=None, g=16):
+    return _check(lib().qtip_block_ldl(_ptr(H), n, g, _ptr(A_out), _ptr(D_out), _ptr(workspace),
                                        workspace_bytes, _stream(stream)))
 
 

@@ -226,23 +226,24 @@ size_t qtip_block_ldl_workspace(int n) {
     return qtip::block_ldl_workspace(n);
 }
 
-int qtip_block_ldl(const double *H, int n, float *A_out, double *D_out, void *workspace,
+int qtip_block_ldl(const double *H, int n, int g, float *A_out, double *D_out, void *workspace,
                    size_t workspace_bytes, void *stream) {
     const char *fn = "qtip_block_ldl";
     if (!H || !A_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
+    if (g != 8 && g != 16) return fail(QTIP_EINVAL, "%s: g = %d must be 8 or 16", fn, g);
     if (n <= 0 || n % 16) return fail(QTIP_EINVAL, "%s: n = %d must be a positive multiple of 16", fn, n);
     if ((uintptr_t)H % 8 || (uintptr_t)D_out % 8 || (uintptr_t)A_out % 4 || (uintptr_t)workspace % 256)
         return fail(QTIP_EINVAL, "%s: H, D_out need 8-byte, A_out 4-byte, workspace 256-byte alignment", fn);
     if (workspace_bytes < qtip::block_ldl_workspace(n))
         return fail(QTIP_EINVAL, "%s: workspace of %zu bytes, %zu needed", fn, workspace_bytes,
                     qtip::block_ldl_workspace(n));
-    hipError_t e = qtip::launch_block_ldl(H, n, A_out, D_out, workspace, (hipStream_t)stream);
+    hipError_t e = qtip::launch_block_ldl(H, n, g, A_out, D_out, workspace, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(fn, e);
     return QTIP_OK;
 }
 
 size_t qtip_quantize_ldlq_workspace(int m, int n, int k, int V, long tiles) {
-    if (k < 2 || k > 4 || (V != 1 && V != 2) || tiles <= 0 || m <= 0 || n <= 0 || m % 16 || n % 16) return 0;
+    if (k < 2 || k > 4 || (V != 1 && V != 2) || tiles <= 0 || m <= 0 || n <= 0 || m % 16 || n % 8) return 0;
     return qtip::quantize_ldlq_workspace(m, n, k, V, tiles);
 }
 
@@ -252,7 +253,6 @@ int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int 
     const char *fn = "qtip_quantize_ldlq";
     if (!W || !A || !codes_out || !workspace) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (int rc = check_code(fn, L, k, V, code_id, lut_f16, m, n)) return rc;
-    if (is_lut(code_id)) return fail(QTIP_EUNSUPPORTED, "%s: the lookup-only code is not built here", fn);
     if (((uintptr_t)W | (uintptr_t)A | (uintptr_t)codes_out | (uintptr_t)What_out | (uintptr_t)tile_err) % 4 ||
         (uintptr_t)workspace % 256)
         return fail(QTIP_EINVAL, "%s: arrays need 4-byte, workspace 256-byte alignment", fn);

@@ -45,7 +45,7 @@ hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n,
 
 // BlockLDLQ (qtip_ldlq.hip): block LDL decomposition in binary64 and Algorithm 5's loop.
 size_t block_ldl_workspace(int n);
-hipError_t launch_block_ldl(const double *H, int n, float *A, double *Dout, void *ws, hipStream_t st);
+hipError_t launch_block_ldl(const double *H, int n, int g, float *A, double *Dout, void *ws, hipStream_t st);
 size_t quantize_ldlq_workspace(int m, int n, int k, int V, long tiles);
 hipError_t launch_quantize_ldlq(int k, int V, int code_id, const float *W, const float *A, int m, int n,
                                 const uint32_t *lut, uint32_t *codes, float *What, float *tile_err,

@@ -1,5 +1,7 @@
-// BlockLDLQ with the trellis quantizer as its rounder (Algorithm 5 of arXiv 2406.11235,
-// T_x = T_y = 16): the block LDL decomposition of the proxy Hessian and the loop over
+// BlockLDLQ with the trellis quantizer as its rounder (Algorithm 5 of arXiv 2406.11235;
+// T_x = T_y = 16 for the codes of Algorithms 1-3, T_x = 32 and T_y = 8 for the lookup-only
+// code, whose smaller group size is the reason the paper gives for that shape; the comments
+// below say 16 for T_y = G): the block LDL decomposition of the proxy Hessian and the loop over
 // column blocks, last to first, that quantizes x = W_j + (W - What)_{>j} A_{>j,j} tile by
 // tile with the GPU Viterbi quantizer and feeds the error of every finished block forward.
 //
@@ -22,7 +24,7 @@
 namespace qtip {
 namespace {
 
-constexpr int G = 16;  // T_y = block size of the decomposition = tile width
+// G = T_y = block size of the decomposition = width of a sequence's block of the matrix
 
 // ------------------------------------------------------------------ block LDL
 
@@ -39,7 +41,8 @@ __global__ void ldl_init_kernel(const double *__restrict__ H, double *__restrict
 // Workgroup b of step j: b = 0 stores D_j; b > 0 computes L_ij = S_ij D_j^-1 for block row
 // i = j + b.  Every workgroup inverts D_j itself (Gauss-Jordan in LDS, no pivoting: the
 // block is symmetric positive definite).
-__global__ __launch_bounds__(256) void ldl_panel_kernel(double *__restrict__ S, double *__restrict__ Lm,
+template <int G>
+__global__ __launch_bounds__(G * G) void ldl_panel_kernel(double *__restrict__ S, double *__restrict__ Lm,
                                                         int n, int j, double *__restrict__ Dout) {
     __shared__ double s_aug[G][2 * G + 1];
     __shared__ double s_t[G][G + 1];
@@ -79,7 +82,8 @@ __global__ __launch_bounds__(256) void ldl_panel_kernel(double *__restrict__ S, 
 
 // S_ik -= L_ij (S_kj)^T for the blocks i >= k > j (D_j is symmetric, so L_ij D_j L_kj^T is
 // L_ij times the transpose of the untouched S_kj = L_kj D_j).
-__global__ __launch_bounds__(256) void ldl_update_kernel(double *__restrict__ S, const double *__restrict__ Lm,
+template <int G>
+__global__ __launch_bounds__(G * G) void ldl_update_kernel(double *__restrict__ S, const double *__restrict__ Lm,
                                                          int n, int j) {
     const int bi = j + 1 + blockIdx.y, bk = j + 1 + blockIdx.x;
     if (bk > bi) return;
@@ -96,7 +100,7 @@ __global__ __launch_bounds__(256) void ldl_update_kernel(double *__restrict__ S,
 }
 
 // A = L - I in binary32: the blocks strictly below the diagonal blocks, zero elsewhere.
-__global__ void ldl_emit_kernel(const double *__restrict__ Lm, float *__restrict__ A, int n) {
+__global__ void ldl_emit_kernel(const double *__restrict__ Lm, float *__restrict__ A, int n, int G) {
     const size_t total = (size_t)n * n;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
          idx += (size_t)gridDim.x * blockDim.x) {
@@ -115,6 +119,7 @@ __global__ void ldl_emit_kernel(const double *__restrict__ Lm, float *__restrict
 // block: that order is the definition both sides use.  A thread owns one column and 8 rows:
 // 16 values of A in registers, the rows' errors are wave-uniform.
 constexpr int UPD_ROWS = 8;
+template <int G>
 __global__ __launch_bounds__(256) void ldlq_update_kernel(const float *__restrict__ Eslab,
                                                           const float *__restrict__ A, int m, int n, int j,
                                                           float *__restrict__ X) {
@@ -143,6 +148,8 @@ __global__ void ldlq_copy_kernel(const float *__restrict__ src, float *__restric
 
 // After block j is quantized: its error slab E_j and What from the decoded slab, and the
 // slab's codes and errors to their places in the matrix's tile order.
+// (TX x G is the block that is one sequence, so the slab holds m / TX of them.)
+template <int G, int TX>
 __global__ __launch_bounds__(256) void ldlq_finish_kernel(const float *__restrict__ W,
                                                           const half_t *__restrict__ slab,
                                                           const uint32_t *__restrict__ slab_codes,
@@ -159,11 +166,11 @@ __global__ __launch_bounds__(256) void ldlq_finish_kernel(const float *__restric
     Eslab[(size_t)r * G + c] = W[at] - w;
     if (What) What[at] = w;
     const int tn = n / G;
-    if (idx < (m / G) * nwords) {
+    if (idx < (m / TX) * nwords) {
         const int I = idx / nwords, wd = idx % nwords;
         codes[((size_t)I * tn + j) * nwords + wd] = slab_codes[idx];
     }
-    if (tile_err && idx < m / G) tile_err[(size_t)idx * tn + j] = slab_err[idx];
+    if (tile_err && idx < m / TX) tile_err[(size_t)idx * tn + j] = slab_err[idx];
 }
 
 size_t align256(size_t b) { return (b + 255) / 256 * 256; }
@@ -172,37 +179,43 @@ size_t align256(size_t b) { return (b + 255) / 256 * 256; }
 
 size_t block_ldl_workspace(int n) { return 2 * align256((size_t)n * n * sizeof(double)); }
 
-hipError_t launch_block_ldl(const double *H, int n, float *A, double *Dout, void *ws, hipStream_t st) {
+template <int G>
+static hipError_t block_ldl_t(const double *H, int n, float *A, double *Dout, void *ws, hipStream_t st) {
     double *S = (double *)ws;
     double *Lm = (double *)((char *)ws + align256((size_t)n * n * sizeof(double)));
     const int nb = n / G;
     hipLaunchKernelGGL(ldl_init_kernel, dim3(1024), dim3(256), 0, st, H, S, Lm, n);
     for (int j = 0; j < nb; j++) {
-        hipLaunchKernelGGL(ldl_panel_kernel, dim3(nb - j), dim3(256), 0, st, S, Lm, n, j, Dout);
+        hipLaunchKernelGGL(ldl_panel_kernel<G>, dim3(nb - j), dim3(G * G), 0, st, S, Lm, n, j, Dout);
         if (j + 1 < nb)
-            hipLaunchKernelGGL(ldl_update_kernel, dim3(nb - j - 1, nb - j - 1), dim3(256), 0, st, S,
+            hipLaunchKernelGGL(ldl_update_kernel<G>, dim3(nb - j - 1, nb - j - 1), dim3(G * G), 0, st, S,
                                (const double *)Lm, n, j);
     }
-    hipLaunchKernelGGL(ldl_emit_kernel, dim3(1024), dim3(256), 0, st, (const double *)Lm, A, n);
+    hipLaunchKernelGGL(ldl_emit_kernel, dim3(1024), dim3(256), 0, st, (const double *)Lm, A, n, G);
     return hipGetLastError();
 }
 
-// Workspace of the loop: the running sum X (m x n), the error slab (m x 16), the decoded
-// slab (fp16 m x 16), the slab's codes and errors, then the Viterbi quantizer's own workspace.
-static size_t ldlq_fixed_bytes(int m, int n, int k) {
+hipError_t launch_block_ldl(const double *H, int n, int g, float *A, double *Dout, void *ws, hipStream_t st) {
+    return g == 8 ? block_ldl_t<8>(H, n, A, Dout, ws, st) : block_ldl_t<16>(H, n, A, Dout, ws, st);
+}
+
+// Workspace of the loop: the running sum X (m x n), the error slab (m x G), the decoded
+// slab (fp16 m x G), the slab's codes and errors, then the Viterbi quantizer's own workspace.
+static size_t ldlq_fixed_bytes(int m, int n, int k, int G, int TX) {
     return align256((size_t)m * n * 4) + align256((size_t)m * G * 4) + align256((size_t)m * G * 2) +
-           align256((size_t)(m / G) * 8 * k * 4) + align256((size_t)(m / G) * 4);
+           align256((size_t)(m / TX) * 8 * k * 4) + align256((size_t)(m / TX) * 4);
 }
 
+// (sized for 16 x 16 blocks, which is also enough for 32 x 8)
 size_t quantize_ldlq_workspace(int m, int n, int k, int V, long tiles) {
-    if (tiles > m / G) tiles = m / G;
-    return ldlq_fixed_bytes(m, n, k) + quantize_gpu_workspace(k, V, tiles);
+    if (tiles > m / 16) tiles = m / 16;
+    return ldlq_fixed_bytes(m, n, k, 16, 16) + quantize_gpu_workspace(k, V, tiles);
 }
 
-hipError_t launch_quantize_ldlq(int k, int V, int code_id, const float *W, const float *A, int m, int n,
-                                const uint32_t *lut, uint32_t *codes, float *What, float *tile_err,
-                                void *ws, size_t ws_bytes, hipStream_t st) {
-    (void)V;
+template <int G, int TX>
+static hipError_t quantize_ldlq_t(int k, int code_id, const float *W, const float *A, int m, int n,
+                                  const uint32_t *lut, uint32_t *codes, float *What, float *tile_err,
+                                  void *ws, size_t ws_bytes, hipStream_t st) {
     char *p = (char *)ws;
     float *X = (float *)p;
     p += align256((size_t)m * n * 4);
@@ -211,10 +224,10 @@ hipError_t launch_quantize_ldlq(int k, int V, int code_id, const float *W, const
     half_t *slab = (half_t *)p;
     p += align256((size_t)m * G * 2);
     uint32_t *slab_codes = (uint32_t *)p;
-    p += align256((size_t)(m / G) * 8 * k * 4);
+    p += align256((size_t)(m / TX) * 8 * k * 4);
     float *slab_err = (float *)p;
-    p += align256((size_t)(m / G) * 4);
-    const size_t fixed = ldlq_fixed_bytes(m, n, k);
+    p += align256((size_t)(m / TX) * 4);
+    const size_t fixed = ldlq_fixed_bytes(m, n, k, G, TX);
     if (ws_bytes <= fixed) return hipErrorInvalidValue;
     const size_t qbytes = ws_bytes - fixed;
     const int nwords = 8 * k;
@@ -227,16 +240,25 @@ hipError_t launch_quantize_ldlq(int k, int V, int code_id, const float *W, const
         if (e != hipSuccess) return e;
         e = launch_dequantize(k, code_id, slab_codes, lut, m, G, slab, st);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(ldlq_finish_kernel, egrid, dim3(256), 0, st, W, (const half_t *)slab,
+        hipLaunchKernelGGL((ldlq_finish_kernel<G, TX>), egrid, dim3(256), 0, st, W, (const half_t *)slab,
                            (const uint32_t *)slab_codes, (const float *)slab_err, m, n, j, nwords, Eslab, What,
                            codes, tile_err);
         if (j > 0)
-            hipLaunchKernelGGL(ldlq_update_kernel, dim3((j * G + 255) / 256, (m + UPD_ROWS - 1) / UPD_ROWS),
+            hipLaunchKernelGGL(ldlq_update_kernel<G>, dim3((j * G + 255) / 256, (m + UPD_ROWS - 1) / UPD_ROWS),
                                dim3(256), 0, st, (const float *)Eslab, A, m, n, j, X);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+hipError_t launch_quantize_ldlq(int k, int V, int code_id, const float *W, const float *A, int m, int n,
+                                const uint32_t *lut, uint32_t *codes, float *What, float *tile_err,
+                                void *ws, size_t ws_bytes, hipStream_t st) {
+    (void)V;
+    if (code_id == CODE_LUT)
+        return quantize_ldlq_t<8, 32>(k, code_id, W, A, m, n, lut, codes, What, tile_err, ws, ws_bytes, st);
+    return quantize_ldlq_t<16, 16>(k, code_id, W, A, m, n, lut, codes, What, tile_err, ws, ws_bytes, st);
 }
 
 }  // namespace qtip

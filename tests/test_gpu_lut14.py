@@ -206,6 +206,11 @@ def test_error_codes(q):
         q.qtip_decode_matvec(codes, 14, 2, 2, CODE_LUT, lut, 32, 64, X, Y)
     with pytest.raises(q.QtipError, match="L = 14"):
         q.qtip_decode_matvec(codes, 14, 2, 1, synth.CODE_3INST, None, 32, 64, X, Y)
+    H = torch.eye(32, dtype=torch.float64, device="cuda")
+    A = torch.zeros((32, 32), dtype=torch.float32, device="cuda")
+    ws = torch.empty(q.qtip_block_ldl_workspace(32), dtype=torch.uint8, device="cuda")
+    with pytest.raises(q.QtipError, match="8 or 16"):
+        q.qtip_block_ldl(H, 32, A, None, ws, ws.numel(), g=12)
 
 
 # ------------------------------------------------------------------ quantizer
@@ -273,3 +278,91 @@ def test_quantizer_roundtrip_and_distortion(q):
     # between Table 1's L = 16 random-table entry (0.068) and Table 2's L = 12 entry (0.0733), give or
     # take the noise of 8192 samples
     assert 0.066 < mse < 0.076, mse
+
+
+# ------------------------------------------------------------------ BlockLDLQ, T_y = 8
+
+def random_spd(rng, n, samples=None, corr=0.9):
+    samples = samples or 4 * n
+    base = rng.standard_normal((samples, 1))
+    X = corr * base + (1 - corr) * rng.standard_normal((samples, n))
+    X = X * rng.uniform(0.5, 2.0, n)[None, :]
+    return X.T @ X / samples + 1e-3 * np.eye(n)
+
+
+def run_block_ldl8(q, H):
+    import torch
+    n = H.shape[0]
+    A = torch.full((n, n), float("nan"), dtype=torch.float32, device="cuda")
+    D = torch.full((n // 8, 8, 8), float("nan"), dtype=torch.float64, device="cuda")
+    wsb = q.qtip_block_ldl_workspace(n)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    q.qtip_block_ldl(dev(np.ascontiguousarray(H, dtype=np.float64)), n, A, D, ws, wsb, g=8)
+    torch.cuda.synchronize()
+    return A.cpu().numpy(), D.cpu().numpy()
+
+
+def run_ldlq(q, W, A, k, lut, tiles=None):
+    import torch
+    m, n = W.shape
+    ntiles = (m // 32) * (n // 8)
+    wsb = q.qtip_quantize_ldlq_workspace(m, n, k, 1, tiles or m // 32)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    codes = torch.full((ntiles, 8 * k), -1, dtype=torch.int32, device="cuda")
+    What = torch.full((m, n), float("nan"), dtype=torch.float32, device="cuda")
+    err = torch.full((ntiles,), float("nan"), dtype=torch.float32, device="cuda")
+    q.qtip_quantize_ldlq(dev(np.ascontiguousarray(W, dtype=np.float32)), dev(np.ascontiguousarray(A, dtype=np.float32)),
+                         m, n, 14, k, 1, CODE_LUT, dev(lut), codes, What, err, ws, wsb)
+    torch.cuda.synchronize()
+    return codes.cpu().numpy().view(np.uint32), What.cpu().numpy(), err.cpu().numpy()
+
+
+@pytest.mark.parametrize("n", [16, 48, 272])
+def test_block_ldl_with_groups_of_8(q, n):
+    rng = np.random.default_rng(800 + n)
+    H = random_spd(rng, n)
+    A, D = run_block_ldl8(q, H)
+    Lm, Dref = oracle.block_ldl(H, 8)
+    Aref = Lm - np.eye(n)
+    assert np.all(np.isfinite(A)) and np.all(np.isfinite(D))
+    for j in range(n // 8):
+        assert np.all(A[8 * j:8 * j + 8, 8 * j:] == 0)
+    assert np.abs(A - Aref).max() <= 1e-6 * max(1.0, np.abs(Aref).max())
+    assert np.allclose(D, Dref, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_ldlq_streams_equal_the_oracle_loop(q, k):
+    """Algorithm 5 with T_x = 32, T_y = 8: the same feedback matrix on both sides, streams,
+    decoded weights and reported errors bit for bit."""
+    rng = np.random.default_rng(900 + k)
+    lut = rng.standard_normal(1 << 14).astype(np.float16)
+    C = oracle.codebook(14, 1, CODE_LUT, lut)
+    m, n = 64, 40
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    Lm, _ = oracle.block_ldl(random_spd(rng, n), 8)
+    A = (Lm - np.eye(n)).astype(np.float32)
+    codes_ref, What_ref, xs = oracle.ldlq_quantize_f32(W, A, 14, k, 1, CODE_LUT, lut, tile=TILE)
+    codes, What, err = run_ldlq(q, W, A, k, lut, tiles=1)
+    assert np.array_equal(codes, codes_ref)
+    assert np.array_equal(What, What_ref)
+    tn = n // 8
+    for t in range(codes.shape[0]):
+        I, j = t // tn, t % tn
+        d, _ = oracle.tailbiting_quantize_f32(xs[32 * I:32 * I + 32, 8 * j:8 * j + 8].reshape(-1), 14, k, 1, C)
+        assert err[t] == d
+
+
+def test_ldlq_lowers_the_proxy_loss(q):
+    rng = np.random.default_rng(909)
+    lut = rng.standard_normal(1 << 14).astype(np.float16)
+    m, n = 128, 256
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    H = random_spd(rng, n, corr=0.95)
+    A, _ = run_block_ldl8(q, H)
+    codes, What, err = run_ldlq(q, W, A, 2, lut)
+    Wd = oracle.dequantize(codes, 14, 2, 1, CODE_LUT, m, n, lut, tile=TILE).view(np.float16).astype(np.float32)
+    assert np.array_equal(What, Wd)
+    _, What0, _ = run_ldlq(q, W, np.zeros((n, n), np.float32), 2, lut)
+    loss = lambda Wh: np.trace((Wh - W).astype(np.float64) @ H @ (Wh - W).astype(np.float64).T)
+    assert loss(What) < 0.7 * loss(What0)

@@ -610,14 +610,15 @@ def test_ldlq_feedback_is_the_stated_sum():
     assert abs(float(oracle.ldlq_feedback_f32(W, E, A, 0, g)[r, c]) - float(acc)) <= 2e-6 * abs(float(acc)) + 1e-6
 
 
-def test_ldlq_loop_identities():
+@pytest.mark.parametrize("Tx,Ty", [(16, 16), (32, 8)])
+def test_ldlq_loop_identities(Tx, Ty):
     """With any rounder, Algorithm 5 satisfies (W - What) L = x - What block by block, which is
     what turns the proxy loss into a sum over blocks: tr(E H E^T) = sum_j tr(eta_j D_j eta_j^T)."""
     rng = np.random.default_rng(21)
-    m, n = 16, 64
+    m, n = 2 * Tx, 64
     L, k, V = 8, 2, 1
     H = _random_spd(rng, n)
-    Lm, D = oracle.block_ldl(H, 16)
+    Lm, D = oracle.block_ldl(H, Ty)
     A = (Lm - np.eye(n)).astype(np.float32)
     W = rng.standard_normal((m, n)).astype(np.float32)
     C8 = rng.standard_normal((1 << L, V)).astype(np.float16).astype(np.float64)
@@ -629,19 +630,21 @@ def test_ldlq_loop_identities():
     orig = o.codebook
     try:
         o.codebook = lambda *a, **kw: C8                     # a table code at L = 8 keeps this fast
-        codes, What, xs = o.ldlq_quantize_f32(W, A, L, k, V, CODE_3INST, rounder=rounder)
+        codes, What, xs = o.ldlq_quantize_f32(W, A, L, k, V, CODE_3INST, rounder=rounder, tile=(Tx, Ty))
     finally:
         o.codebook = orig
     E = W.astype(np.float64) - What
     eta = xs.astype(np.float64) - What
     assert np.allclose(E @ (np.eye(n) + A.astype(np.float64)), eta, rtol=1e-4, atol=1e-4)
     proxy = np.trace(E @ H @ E.T)
-    blocks = sum(np.trace(eta[:, 16 * j:16 * j + 16] @ D[j] @ eta[:, 16 * j:16 * j + 16].T) for j in range(n // 16))
+    blocks = sum(np.trace(eta[:, Ty * j:Ty * j + Ty] @ D[j] @ eta[:, Ty * j:Ty * j + Ty].T) for j in range(n // Ty))
     assert abs(proxy - blocks) <= 1e-3 * proxy
-    # every block of What is the decode of its own stream
-    for j in range(n // 16):
-        vals, _ = oracle.decode_sequence_table(codes[j], 256, L, k, V, C8)
-        assert np.array_equal(What[:, 16 * j:16 * j + 16], vals.reshape(16, 16).astype(np.float32))
+    # every block of What is the decode of its own stream (sequence I (n / T_y) + j, row-major T_x x T_y)
+    for I in range(m // Tx):
+        for j in range(n // Ty):
+            vals, _ = oracle.decode_sequence_table(codes[I * (n // Ty) + j], 256, L, k, V, C8)
+            assert np.array_equal(What[Tx * I:Tx * I + Tx, Ty * j:Ty * j + Ty],
+                                  vals.reshape(Tx, Ty).astype(np.float32))
 
 
 def test_ldlq_without_correlation_is_plain_quantization_and_feedback_helps():
