@@ -27,11 +27,18 @@
  *           half-word 2*idx + v.  Bit 15 of the hash negates entry v = 1 (the
  *           "second entry" of Section 3.1.2).  4-byte aligned.
  *   fp16    IEEE binary16, passed as void*.
+ *   QTIP_CODE_LUT (the lookup-only code of the appendix on lookup-only codes) differs in
+ *           three places: L = 14; the sequence of 256 weights is a 32 x 8 block
+ *           (T_x = 32 outputs, T_y = 8 inputs), so the matrix is a row-major array of
+ *           32 x 8 blocks, block (I, J) at word (I*(n/8) + J) * 8k, its element s at
+ *           W~[32I + s/8][8J + s%8]; lut is the code itself, 2^14 fp16 values, DEVICE
+ *           memory, 16-byte aligned, the value of state x at half-word x.
  *
  * SUPPORTED PARAMETERS
- *   L = 16 only.  code_id QTIP_CODE_1MAD / QTIP_CODE_3INST with V = 1 and
- *   k in {2, 3, 4}; QTIP_CODE_HYB and QTIP_CODE_HYB2 (Q = 9) with V = 2 and k in {2, 3, 4}.
- *   m and n multiples of 16.  Anything else returns QTIP_EUNSUPPORTED / QTIP_EINVAL.
+ *   code_id QTIP_CODE_1MAD / QTIP_CODE_3INST with L = 16, V = 1 and k in {2, 3, 4};
+ *   QTIP_CODE_HYB and QTIP_CODE_HYB2 (Q = 9) with L = 16, V = 2 and k in {2, 3, 4}; m and n
+ *   multiples of 16.  QTIP_CODE_LUT with L = 14, V = 1 and k in {2, 3, 4}; m a multiple of
+ *   32, n of 8.  Anything else returns QTIP_EUNSUPPORTED / QTIP_EINVAL.
  *
  * OWNERSHIP, STREAMS, ERRORS
  *   The caller owns every buffer.  GPU entry points take device pointers, enqueue
@@ -95,7 +102,7 @@ int qtip_rht_f32(const float *x_f32, const int8_t *signs, int n, int block, int 
  * x_f16: device, n fp16 (normally the output of qtip_rht side 0).  y: device, m
  * fp32, overwritten.  Decoded weights are exactly the fp16 values of
  * qtip_dequantize; products are accumulated in fp32.  lut_f16 is NULL unless
- * code_id is QTIP_CODE_HYB.
+ * the code has a table (QTIP_CODE_HYB, QTIP_CODE_HYB2, QTIP_CODE_LUT).
  */
 int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
                        const void *lut_f16, int m, int n, const void *x_f16, float *y,
@@ -107,7 +114,8 @@ int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
  * overwritten.  row_scale_f16: device, m fp16, or NULL for no scale.  B >= 1.
  * Small B runs on the vector ALUs, larger B on the matrix cores (MFMA) with the
  * decoded 16x16 tile as one operand (Section 4: T_x = T_y = 16 matches a 16x16
- * matrix-multiply tile).
+ * matrix-multiply tile).  With QTIP_CODE_LUT every B >= 2 runs on the matrix cores: two
+ * neighbouring 32 x 8 blocks are the 32 x 16 operand of the 32x32x16 instruction.
  */
 int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id,
                        const void *lut_f16, int m, int n, const void *X_f16, int B,
@@ -123,7 +131,8 @@ int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id,
  * from 14.9 to 8.9 us per call).  Larger layers have several workgroups per CU and would
  * redo the transform too often: there the call enqueues the two kernels and needs
  * xt_scratch (device, n fp16, 16-byte aligned; may be NULL otherwise) for the transformed
- * vector.  Together with qtip_rht_f32(side 1) on y a small layer is two launches.
+ * vector (QTIP_CODE_LUT always takes this two-kernel form: its workgroups fill their LDS
+ * with the table).  Together with qtip_rht_f32(side 1) on y a small layer is two launches.
  *   x_f16: device, n fp16, untransformed.  signs_n: device, n int8 in {+1,-1}.
  *   block: Hadamard block (as qtip_rht).  row_scale_f16: device m fp16 or NULL.
  */
