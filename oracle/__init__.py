@@ -18,7 +18,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qtip_oracle.c")
 _LIB = os.path.join(_HERE, "libqtip_oracle.so")
 
-CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT = 0, 1, 2, 3, 4
+CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT, CODE_HYB1 = 0, 1, 2, 3, 4, 5
+
+
+def _q(code_id, Q):
+    """Index bits of the hash codes: 9 for HYB (Section 4.2), 6 for its V = 1 form."""
+    return (6 if code_id == CODE_HYB1 else 9) if Q is None else Q
 
 
 def build(force=False):
@@ -58,6 +63,8 @@ def lib():
         L.orc_code_hyb.argtypes = [c.c_uint32, i32, vp, vp]
         L.orc_code_hyb2.restype = None
         L.orc_code_hyb2.argtypes = [c.c_uint32, i32, vp, vp]
+        L.orc_code_hyb1.restype = c.c_uint16
+        L.orc_code_hyb1.argtypes = [c.c_uint32, i32, vp]
         L.orc_codebook.restype = i32
         L.orc_codebook.argtypes = [i32, i32, i32, vp, i32, vp]
         L.orc_decode_sequence.restype = None
@@ -179,21 +186,27 @@ def code_hyb2(x, lut, Q=9):
     return int(out[0]), int(out[1])
 
 
-def codebook(L, V, code_id, lut=None, Q=9):
+def code_hyb1(x, lut, Q=6):
+    lut = _u16(lut).reshape(-1)
+    assert lut.size == 1 << Q
+    return int(lib().orc_code_hyb1(int(x), Q, _p(lut)))
+
+
+def codebook(L, V, code_id, lut=None, Q=None):
     """C[2^L][V] as float64, by evaluating the code on every state."""
     lut = None if lut is None else _u16(lut).reshape(-1)
     C = np.zeros((1 << L, V), dtype=np.float64)
-    rc = lib().orc_codebook(L, V, code_id, _p(lut), Q, _p(C))
+    rc = lib().orc_codebook(L, V, code_id, _p(lut), _q(code_id, Q), _p(C))
     assert rc == 0
     return C
 
 
-def decode_sequence(words, T, L, k, V, code_id, lut=None, Q=9):
+def decode_sequence(words, T, L, k, V, code_id, lut=None, Q=None):
     w = _u32(words)
     assert w.size * 32 >= k * T
     lut = None if lut is None else _u16(lut).reshape(-1)
     out = np.zeros(T, dtype=np.uint16)
-    lib().orc_decode_sequence(_p(w), T, L, k, V, code_id, _p(lut), Q, _p(out))
+    lib().orc_decode_sequence(_p(w), T, L, k, V, code_id, _p(lut), _q(code_id, Q), _p(out))
     return out
 
 
@@ -207,22 +220,22 @@ def decode_sequence_table(words, T, L, k, V, C):
     return out, st
 
 
-def dequantize(codes, L, k, V, code_id, m, n, lut=None, Q=9, tile=(16, 16)):
+def dequantize(codes, L, k, V, code_id, m, n, lut=None, Q=None, tile=(16, 16)):
     """Dense decoded weights as uint16 fp16 bit patterns, shape (m, n); tile = (T_x, T_y)."""
     Tx, Ty = tile
     codes = _u32(codes).reshape(-1)
     assert codes.size == (m // Tx) * (n // Ty) * 8 * k
     lut = None if lut is None else _u16(lut).reshape(-1)
     W = np.zeros((m, n), dtype=np.uint16)
-    rc = lib().orc_dequantize_tiled(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, Tx, Ty, _p(W))
+    rc = lib().orc_dequantize_tiled(_p(codes), L, k, V, code_id, _p(lut), _q(code_id, Q), m, n, Tx, Ty, _p(W))
     assert rc == 0
     return W
 
 
-def decode_element(codes, L, k, V, code_id, n, i, j, lut=None, Q=9, tile=(16, 16)):
+def decode_element(codes, L, k, V, code_id, n, i, j, lut=None, Q=None, tile=(16, 16)):
     codes = _u32(codes).reshape(-1)
     lut = None if lut is None else _u16(lut).reshape(-1)
-    return int(lib().orc_decode_element_tiled(_p(codes), L, k, V, code_id, _p(lut), Q, n, tile[0], tile[1],
+    return int(lib().orc_decode_element_tiled(_p(codes), L, k, V, code_id, _p(lut), _q(code_id, Q), n, tile[0], tile[1],
                                               i, j))
 
 
@@ -238,7 +251,7 @@ def matmat_dense(W, X, scale=None):
     return Y
 
 
-def decode_matmat_rows(codes, L, k, V, code_id, m, n, X, rows, lut=None, Q=9, scale=None, tile=(16, 16)):
+def decode_matmat_rows(codes, L, k, V, code_id, m, n, X, rows, lut=None, Q=None, scale=None, tile=(16, 16)):
     """fp64 outputs for the chosen rows only: shape (B, len(rows))."""
     codes = _u32(codes).reshape(-1)
     lut = None if lut is None else _u16(lut).reshape(-1)
@@ -247,7 +260,7 @@ def decode_matmat_rows(codes, L, k, V, code_id, m, n, X, rows, lut=None, Q=9, sc
     rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
     scale = _u16(scale)
     Y = np.zeros((B, rows.size), dtype=np.float64)
-    lib().orc_decode_matmat_rows_tiled(_p(codes), L, k, V, code_id, _p(lut), Q, m, n, tile[0], tile[1],
+    lib().orc_decode_matmat_rows_tiled(_p(codes), L, k, V, code_id, _p(lut), _q(code_id, Q), m, n, tile[0], tile[1],
                                        _p(X), B, _p(scale), _p(rows), rows.size, _p(Y))
     return Y
 

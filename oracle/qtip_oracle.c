@@ -12,7 +12,7 @@
  *   - the packed bitstream and the L-bit state window of the bitshift
  *     trellis (Section 3.1; Figure 1; tail-biting wrap, Section 3.2);
  *   - the state -> value codes 1MAD (Algorithm 1), 3INST (Algorithm 2) and
- *     HYB (Algorithm 3) and its two-sign-flip form, plus a plain table code
+ *     HYB (Algorithm 3), its two-sign-flip form and its V = 1 form, plus a plain table code
  *     C[2^L][V] (Section 2.3) and the lookup-only code of the appendix on
  *     lookup-only codes (a stored fp16 table of 2^L entries, V = 1);
  *   - decode of a tile and of a whole matrix (Section 4: a T_x x T_y
@@ -55,6 +55,7 @@
 #define ORC_CODE_HYB 2
 #define ORC_CODE_HYB2 3
 #define ORC_CODE_LUT 4 /* lookup-only: the value of a state is table entry [state] */
+#define ORC_CODE_HYB1 5 /* Algorithm 3 with V = 1 (the Q = 6 one-dimensional table of Section 4.2's remark) */
 
 int orc_threads(void) {
 #ifdef _OPENMP
@@ -189,6 +190,21 @@ void orc_code_hyb2(uint32_t x, int Q, const uint16_t *lut, uint16_t out[2]) {
     if ((X >> 15) & 1u) out[1] ^= 0x8000u;
 }
 
+/*
+ * Algorithm 3 with V = 1 (the paper names it with Q = 6 as a fit for hardware
+ * with a 64-entry table lookup): the same hash, Q index bits from bit 15-Q
+ * upward into a table of 2^Q single fp16 values, and bit 15 of the hash flips
+ * the sign of the looked-up value (with one entry per row, "the second entry"
+ * of the V = 2 form can only be the entry itself).
+ */
+uint16_t orc_code_hyb1(uint32_t x, int Q, const uint16_t *lut) {
+    uint32_t X = x * x + x;
+    uint32_t idx = (X >> (15 - Q)) & ((1u << Q) - 1u);
+    uint16_t v = lut[idx];
+    if ((X >> 15) & 1u) v ^= 0x8000u;
+    return v;
+}
+
 /* One state -> V fp16 values for the given code. */
 static void orc_code_eval(int code_id, uint32_t state, const uint16_t *lut, int Q,
                           uint16_t *out) {
@@ -200,6 +216,8 @@ static void orc_code_eval(int code_id, uint32_t state, const uint16_t *lut, int 
         orc_code_hyb2(state, Q, lut, out);
     else if (code_id == ORC_CODE_LUT)
         out[0] = lut[state]; /* Section 2.3's plain table, 2^L fp16 entries (V = 1) */
+    else if (code_id == ORC_CODE_HYB1)
+        out[0] = orc_code_hyb1(state, Q, lut);
     else
         orc_code_hyb(state, Q, lut, out);
 }

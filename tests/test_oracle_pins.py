@@ -196,6 +196,31 @@ def test_hyb_index_and_sign(golden):
     assert flips == 32768
 
 
+def test_hyb_with_one_entry_per_row():
+    """Algorithm 3 at V = 1, Q = 6: index = bits 9..14 of x*x + x, bit 15 negates the value.
+    Everything from Python integers; every one of the 128 signed values is reached, about equally."""
+    from oracle import CODE_HYB1
+    rng = np.random.default_rng(66)
+    lut = rng.standard_normal(64).astype(np.float16)
+    bits = lut.view(np.uint16)
+    C = oracle.codebook(16, 1, CODE_HYB1, lut)
+    counts = np.zeros(128, dtype=int)
+    for x in range(65536):
+        X = (x * x + x) & 0xFFFFFFFF
+        idx, neg = (X >> 9) & 63, (X >> 15) & 1
+        want = int(bits[idx]) ^ (0x8000 if neg else 0)
+        if x % 97 == 0 or x < 64 or x > 65500:
+            assert oracle.code_hyb1(x, lut) == want, x
+        assert C[x, 0] == float(np.uint16(want).view(np.float16)), x
+        counts[idx + 64 * neg] += 1
+    assert counts.min() > 0.8 * 512 and counts.max() < 1.2 * 512
+    # decode of a stream goes through the same function
+    words = rng.integers(0, 1 << 32, 16, dtype=np.uint64).astype(np.uint32)
+    seq = oracle.decode_sequence(words, 256, 16, 2, 1, CODE_HYB1, lut)
+    for t in (0, 7, 200, 255):
+        assert seq[t] == oracle.code_hyb1(oracle.state(words, 512, 16, 2, t), lut)
+
+
 def test_codebook_is_the_code_on_every_state():
     rng = np.random.default_rng(3)
     lut = rng.standard_normal((512, 2)).astype(np.float16)
