@@ -27,6 +27,7 @@
  *           half-word 2*idx + v.  Bit 15 of the hash negates entry v = 1 (the
  *           "second entry" of Section 3.1.2).  4-byte aligned.
  *   fp16    IEEE binary16, passed as void*.
+ *   QTIP_CODE_HYB1: lut is 64 fp16 values, DEVICE memory, 4-byte aligned; L = 16, V = 1.
  *   QTIP_CODE_LUT (the lookup-only code of the appendix on lookup-only codes) differs in
  *           three places: L = 14; the sequence of 256 weights is a 32 x 8 block
  *           (T_x = 32 outputs, T_y = 8 inputs), so the matrix is a row-major array of
@@ -36,7 +37,8 @@
  *
  * SUPPORTED PARAMETERS
  *   code_id QTIP_CODE_1MAD / QTIP_CODE_3INST with L = 16, V = 1 and k in {2, 3, 4};
- *   QTIP_CODE_HYB and QTIP_CODE_HYB2 (Q = 9) with L = 16, V = 2 and k in {2, 3, 4}; m and n
+ *   QTIP_CODE_HYB and QTIP_CODE_HYB2 (Q = 9) with L = 16, V = 2 and k in {2, 3, 4};
+ *   QTIP_CODE_HYB1 (Q = 6) with L = 16, V = 1 and k in {2, 3, 4}; m and n
  *   multiples of 16.  QTIP_CODE_LUT with L = 14, V = 1 and k in {2, 3, 4}; m a multiple of
  *   32, n of 8.  Anything else returns QTIP_EUNSUPPORTED / QTIP_EINVAL.
  *
@@ -73,6 +75,9 @@ extern "C" {
 #define QTIP_CODE_HYB2 3  /* the same with bit 31 of the hash also XORed (Section 3.1.2): the first
                              entry gets a sign of its own; for L = 16 that bit is set exactly when
                              the state is at least 46341 */
+#define QTIP_CODE_HYB1 5  /* Algorithm 3 with one entry per row: L = 16, V = 1, Q = 6 (Section 4.2's remark
+                             on hardware with a 64-entry table lookup): bits 9..14 of the hash index
+                             64 fp16 values, bit 15 negates the value */
 #define QTIP_CODE_LUT 4   /* lookup-only code (appendix on lookup-only codes): L = 14, V = 1, the value
                              of a state is entry [state] of a stored table; T_x = 32, T_y = 8 */
 
@@ -102,7 +107,7 @@ int qtip_rht_f32(const float *x_f32, const int8_t *signs, int n, int block, int 
  * x_f16: device, n fp16 (normally the output of qtip_rht side 0).  y: device, m
  * fp32, overwritten.  Decoded weights are exactly the fp16 values of
  * qtip_dequantize; products are accumulated in fp32.  lut_f16 is NULL unless
- * the code has a table (QTIP_CODE_HYB, QTIP_CODE_HYB2, QTIP_CODE_LUT).
+ * the code has a table (QTIP_CODE_HYB, QTIP_CODE_HYB2, QTIP_CODE_HYB1, QTIP_CODE_LUT).
  */
 int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
                        const void *lut_f16, int m, int n, const void *x_f16, float *y,

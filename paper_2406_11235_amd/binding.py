@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT = 0, 1, 2, 3, 4
+CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT, CODE_HYB1 = 0, 1, 2, 3, 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # QTIP_LIBRARY points at another build of the same library (e.g. to compare two builds)
@@ -163,7 +163,7 @@ def qtip_quantize(W, m, n, L, k, V, code_id, lut=None):
     assert W.shape == (m, n)
     if lut is not None:
         lut = np.ascontiguousarray(lut)
-        assert lut.dtype in (np.float16, np.uint16) and lut.size == (1 << 14 if code_id == CODE_LUT else 1024)
+        assert lut.dtype in (np.float16, np.uint16) and lut.size == {CODE_LUT: 1 << 14, CODE_HYB1: 64}.get(code_id, 1024)
     codes = np.zeros((m * n // 256, 8 * k), dtype=np.uint32)  # one sequence per 256 weights
     mse = ctypes.c_double(0.0)
     _check(lib().qtip_quantize(_ptr(W), m, n, L, k, V, code_id, _ptr(lut), _ptr(codes),

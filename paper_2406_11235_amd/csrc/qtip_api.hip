@@ -11,6 +11,7 @@ namespace {
 
 bool is_hyb(int code_id) { return code_id == QTIP_CODE_HYB || code_id == QTIP_CODE_HYB2; }
 bool is_lut(int code_id) { return code_id == QTIP_CODE_LUT; }
+bool has_table(int code_id) { return is_hyb(code_id) || is_lut(code_id) || code_id == QTIP_CODE_HYB1; }
 
 thread_local char g_err[512] = "";
 
@@ -32,7 +33,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 // matrix shape: shared by every call that reads or writes a code stream.
 int check_code(const char *fn, int L, int k, int V, int code_id, const void *lut, int m, int n) {
     if (code_id != QTIP_CODE_1MAD && code_id != QTIP_CODE_3INST && code_id != QTIP_CODE_HYB &&
-        code_id != QTIP_CODE_HYB2 && code_id != QTIP_CODE_LUT)
+        code_id != QTIP_CODE_HYB2 && code_id != QTIP_CODE_LUT && code_id != QTIP_CODE_HYB1)
         return fail(QTIP_EUNSUPPORTED, "%s: unknown code_id %d", fn, code_id);
     const int wantL = is_lut(code_id) ? 14 : 16;
     if (L != wantL)
@@ -41,7 +42,7 @@ int check_code(const char *fn, int L, int k, int V, int code_id, const void *lut
     const int wantV = is_hyb(code_id) ? 2 : 1;
     if (V != wantV)
         return fail(QTIP_EUNSUPPORTED, "%s: V = %d (code %d needs V = %d)", fn, V, code_id, wantV);
-    if ((is_hyb(code_id) || is_lut(code_id)) && !lut) return fail(QTIP_EINVAL, "%s: code %d needs a lut", fn, code_id);
+    if (has_table(code_id) && !lut) return fail(QTIP_EINVAL, "%s: code %d needs a lut", fn, code_id);
     if (lut && !aligned(lut, is_lut(code_id) ? 16 : 4))
         return fail(QTIP_EINVAL, "%s: lut must be %d-byte aligned", fn, is_lut(code_id) ? 16 : 4);
     // a sequence is a T_x x T_y block of the matrix: 32 x 8 for the lookup-only code, else 16 x 16

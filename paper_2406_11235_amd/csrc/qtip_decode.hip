@@ -40,7 +40,10 @@ __device__ __forceinline__ void decode_row(const uint32_t (&w)[NWD], int rr,
             uint32_t s0 = window16(w, rr * 16 * K + (2 * c) * K);
             uint32_t s1 = window16(w, rr * 16 * K + (2 * c + 1) * K);
             half2_t h;
-            if constexpr (CODE == CODE_3INST) {
+            if constexpr (CODE == CODE_HYB1) {
+                h.x = code_hyb1(s0, reinterpret_cast<const uint16_t *>(lut));
+                h.y = code_hyb1(s1, reinterpret_cast<const uint16_t *>(lut));
+            } else if constexpr (CODE == CODE_3INST) {
                 h.x = code_3inst(s0);
                 h.y = code_3inst(s1);
             } else {
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t *__restr
 #pragma unroll
     for (int rr = 0; rr < RPL; rr++) {
         half2_t h[8];
-        decode_row<K, V, CODE>(w, rr, s_lut, h);
+        decode_row<K, V, CODE>(w, rr, code_is_hyb(CODE) ? s_lut : lut, h);
         uint4 lo = {as_u32(h[0]), as_u32(h[1]), as_u32(h[2]), as_u32(h[3])};
         uint4 hi = {as_u32(h[4]), as_u32(h[5]), as_u32(h[6]), as_u32(h[7])};
         uint4 *dst = reinterpret_cast<uint4 *>(W + (size_t)(16 * I + q * RPL + rr) * n + 16 * J);
@@ -102,6 +105,8 @@ __global__ void decode_states_kernel(const uint32_t *__restrict__ states, int co
         half2_t h = CODE == CODE_HYB2 ? code_hyb2(st, lut) : code_hyb(st, lut);
         out[2 * i] = h.x;
         out[2 * i + 1] = h.y;
+    } else if constexpr (CODE == CODE_HYB1) {
+        out[i] = code_hyb1(st, reinterpret_cast<const uint16_t *>(lut));
     } else if constexpr (CODE == CODE_3INST) {
         out[i] = code_3inst(st);
     } else {
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
                                                          float *__restrict__ y) {
     constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
     constexpr int TPI = 64 / LPT;  // tiles per wave per iteration
-    __shared__ uint32_t s_lut[code_is_hyb(CODE) ? HYB_LDS_WORDS : 1];
+    __shared__ uint32_t s_lut[code_lds_words(CODE)];
     __shared__ float s_part[NW][16];
     __shared__ __attribute__((aligned(16))) half_t s_x[FUSED ? FUSED_MAX_N : 8];
     // room for FUSED_MAX_N values in blocks of any size, each block with its padding
@@ -147,10 +152,7 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
                                  [dst](int idx, half_t v) { dst[idx] = v; });
         }
     }
-    if constexpr (code_is_hyb(CODE)) {
-        stage_signed_lut(lut, s_lut, NW * 64);
-        __syncthreads();
-    }
+    stage_code_table<CODE>(lut, s_lut, NW * 64);
     RowDot<K, CODE> rd;
     rd.init(s_lut);
     const int I = blockIdx.x;
@@ -277,7 +279,7 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
                                                          float *__restrict__ Y) {
     constexpr int R = 2;
     constexpr int NWORDS = 8 * K;
-    __shared__ uint32_t s_lut[code_is_hyb(CODE) ? HYB_LDS_WORDS : 1];
+    __shared__ uint32_t s_lut[code_lds_words(CODE)];
     // one buffer, used twice: in the loop each wave's staging region (SR batch rows at a
     // time, 128 bytes each, padded to 144 so that the row-wise writes and the
     // column-wise reads both spread over the banks), after it the partial sums
@@ -286,10 +288,7 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
     constexpr int STAGE_FLOATS = STAGE ? NW * SR * XST / 4 : 0;
     __shared__ __attribute__((aligned(16))) float s_buf[PART_FLOATS > STAGE_FLOATS ? PART_FLOATS : STAGE_FLOATS];
     float(*s_part)[R][NB][4][64] = reinterpret_cast<float(*)[R][NB][4][64]>(s_buf);
-    if constexpr (code_is_hyb(CODE)) {
-        stage_signed_lut(lut, s_lut, NW * 64);
-        __syncthreads();
-    }
+    stage_code_table<CODE>(lut, s_lut, NW * 64);
     RowDecode<K, CODE> rdec;
     rdec.init(s_lut);
     const int I0 = blockIdx.x * R;
@@ -518,7 +517,11 @@ static hipError_t launch_matmat_t(const uint32_t *codes, const uint32_t *lut, in
 
 #define QTIP_DISPATCH(FN, ...)                                                         \
     do {                                                                               \
-        if (code_id == CODE_HYB2) {                                                    \
+        if (code_id == CODE_HYB1) {                                                    \
+            if (k == 2) return FN<2, 1, CODE_HYB1>(__VA_ARGS__);                       \
+            if (k == 3) return FN<3, 1, CODE_HYB1>(__VA_ARGS__);                       \
+            return FN<4, 1, CODE_HYB1>(__VA_ARGS__);                                   \
+        } else if (code_id == CODE_HYB2) {                                             \
             if (k == 2) return FN<2, 2, CODE_HYB2>(__VA_ARGS__);                       \
             if (k == 3) return FN<3, 2, CODE_HYB2>(__VA_ARGS__);                       \
             return FN<4, 2, CODE_HYB2>(__VA_ARGS__);                                   \
@@ -570,7 +573,10 @@ hipError_t launch_decode_states(int code_id, const uint32_t *states, int count,
                                 const uint32_t *lut, void *out, hipStream_t st) {
     const int blocks = (count + 255) / 256;
     if (code_id == CODE_LUT) return launch_lut_decode_states(states, count, lut, out, st);
-    if (code_id == CODE_HYB2)
+    if (code_id == CODE_HYB1)
+        hipLaunchKernelGGL((decode_states_kernel<CODE_HYB1>), dim3(blocks), dim3(256), 0, st, states,
+                           count, lut, (half_t *)out);
+    else if (code_id == CODE_HYB2)
         hipLaunchKernelGGL((decode_states_kernel<CODE_HYB2>), dim3(blocks), dim3(256), 0, st, states,
                            count, lut, (half_t *)out);
     else if (code_id == CODE_HYB)

@@ -33,10 +33,15 @@ constexpr int CODE_3INST = 1;
 constexpr int CODE_HYB = 2;
 constexpr int CODE_HYB2 = 3;  // HYB with a second sign flip (bit 31 of the hash on the first entry)
 constexpr int CODE_LUT = 4;   // lookup-only: L = 14, V = 1, 32 x 8 blocks (kernels in qtip_lut14.hip)
+constexpr int CODE_HYB1 = 5;  // Algorithm 3 with one entry per row: V = 1, Q = 6 (64 fp16 values)
 // state bits L and log2 of T_y (a sequence is a (256 / T_y) x T_y block of the matrix)
 __host__ __device__ constexpr int code_state_bits(int code) { return code == CODE_LUT ? 14 : 16; }
 __host__ __device__ constexpr int code_log2_ty(int code) { return code == CODE_LUT ? 3 : 4; }
 __host__ __device__ constexpr bool code_is_hyb(int code) { return code == CODE_HYB || code == CODE_HYB2; }
+// words of LDS the hot loops of a code keep their table in (see stage_code_table)
+__host__ __device__ constexpr int code_lds_words(int code) {
+    return code_is_hyb(code) ? 1024 : code == CODE_HYB1 ? 4096 : 1;
+}
 
 // Section 3.1.1 constants.
 constexpr uint32_t MAD_A = 34038481u, MAD_B = 76625530u;
@@ -134,6 +139,14 @@ __device__ __forceinline__ half2_t code_hyb2(uint32_t x, const uint32_t *lut) {
     uint32_t v = lut[(X >> (15 - HYB_Q)) & ((1u << HYB_Q) - 1u)];
     return as_half2(v ^ ((X & 0x8000u) << 16) ^ ((X >> 16) & 0x8000u));
 }
+// Algorithm 3 with V = 1 and Q = 6: bits 9..14 of the hash index 64 values, bit 15 negates
+// the value.  lut: 64 fp16 bit patterns.
+constexpr int HYB1_Q = 6;
+__device__ __forceinline__ half_t code_hyb1(uint32_t x, const uint16_t *lut) {
+    uint32_t X = x * x + x;
+    uint16_t v = lut[(X >> (15 - HYB1_Q)) & ((1u << HYB1_Q) - 1u)] ^ (uint16_t)(X & 0x8000u);
+    return __builtin_bit_cast(half_t, v);
+}
 // For 16-bit states x*x + x does not wrap, so its bit 31 is set exactly when x >= 46341.
 // Both halves of R are states: bit 15 of each half of the result is that comparison
 // (x >= 46341  <=>  bit 15 of x set and bit 15 of x - 46341 mod 2^16 clear).
@@ -204,6 +217,58 @@ __device__ __forceinline__ void stage_signed_lut(const uint32_t *__restrict__ lu
 __device__ __forceinline__ uint32_t hyb_signed_lookup(const uint32_t *s_lut, uint32_t byte_addr) {
     return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(s_lut) + byte_addr);
 }
+// The V = 1 form in LDS: hash bits 9..15 select one of 128 signed values, and the table is
+// small enough to give every LDS bank a copy of its own: word e * 32 + b holds value e (in
+// both halves) for bank b, and lane l reads bank l % 32, so that no two lanes of a pass ever
+// meet in a bank whatever their states are: 16 KiB buy table reads without bank conflicts.
+__device__ __forceinline__ void stage_hyb1_table(const uint32_t *__restrict__ lut, uint32_t *s_lut,
+                                                 int nthreads) {
+    const uint16_t *lut16 = reinterpret_cast<const uint16_t *>(lut);
+    for (int i = threadIdx.x; i < 128 * 32; i += nthreads) {
+        const int e = i >> 5;
+        const uint32_t v = lut16[e & 63] ^ ((e & 64) ? 0x8000u : 0u);
+        s_lut[i] = v | (v << 16);
+    }
+}
+template <int CODE>
+__device__ __forceinline__ void stage_code_table(const uint32_t *__restrict__ lut, uint32_t *s_lut,
+                                                 int nthreads) {
+    if constexpr (code_is_hyb(CODE)) stage_signed_lut(lut, s_lut, nthreads);
+    if constexpr (CODE == CODE_HYB1) stage_hyb1_table(lut, s_lut, nthreads);
+    if constexpr (code_lds_words(CODE) > 1) __syncthreads();
+}
+// The 16 values of tile row rr of this lane's words for the V = 1 hash code, each in both
+// halves of its register.  lane4 = 4 (lane % 32).
+template <int K, int NW>
+__device__ __forceinline__ void hyb1_row_values(const uint32_t (&w)[NW], int rr, const uint32_t *s_lut,
+                                                uint32_t lane4, uint32_t (&v)[16]) {
+    const int P0 = rr * 16 * K;
+    if constexpr (K == 2 || K == 4) {
+        constexpr int G = 16 / K;  // states between the two halves of a window
+#pragma unroll
+        for (int base = 0; base < 16; base += 2 * G)
+#pragma unroll
+            for (int j = 0; j < G; j++) {
+                const uint32_t R = window32(w, P0 + (base + j) * K);
+                uint32_t H;  // both hashes at once: low 16 bits of x*x + x in each half
+                asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H) : "v"(R));
+                // hash bits 9..15 times 128 bytes, plus this lane's bank
+                v[base + j] = hyb_signed_lookup(s_lut, ((H >> 18) & 0x3F80u) | lane4);
+                v[base + j + G] = hyb_signed_lookup(s_lut, ((H >> 2) & 0x3F80u) | lane4);
+            }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 16; c++) {
+            const uint32_t st = window16(w, P0 + c * K);
+            const uint32_t X = st * st + st;
+            v[c] = hyb_signed_lookup(s_lut, ((X >> 2) & 0x3F80u) | lane4);
+        }
+    }
+}
+// weights c (low half) and c + 1 (high half) as one packed pair
+__device__ __forceinline__ uint32_t hyb1_pair(uint32_t lo, uint32_t hi) {
+    return (hi & 0xFFFF0000u) | (lo & 0xFFFFu);
+}
 
 // acc += p . xa + q . xb for the packed pairs of the previous group, then the next
 // group's four fp16 sums into the same p and q.  Order: the dot products read p and q
@@ -246,7 +311,12 @@ template <int K, int CODE> struct RowDecode {
     }
     template <int NW>
     __device__ __forceinline__ void run(const uint32_t (&w)[NW], int rr, uint32_t (&h)[8]) const {
-        if constexpr (CODE == CODE_3INST) {
+        if constexpr (CODE == CODE_HYB1) {
+            uint32_t v[16];
+            hyb1_row_values<K>(w, rr, lut, (threadIdx.x & 31u) << 2, v);
+#pragma unroll
+            for (int c = 0; c < 8; c++) h[c] = hyb1_pair(v[2 * c], v[2 * c + 1]);
+        } else if constexpr (CODE == CODE_3INST) {
             uint32_t st[16], y[16];
             row_states<K>(w, rr, st);
 #pragma unroll
@@ -435,6 +505,32 @@ template <int K, bool TWO> struct RowDotHyb {
                     if constexpr (TWO) v ^= (X >> 16) & 0x8000u;
                     acc[rr] = __builtin_amdgcn_fdot2(as_half2(v), as_half2(x[c]), acc[rr], false);
                 }
+        }
+    }
+};
+// The V = 1 hash code: per row 16 conflict-free table reads, pipelined by row like HYB.
+template <int K> struct RowDot<K, CODE_HYB1> {
+    const uint32_t *lut;  // LDS: 128 signed values x 32 banks
+    uint32_t lane4;
+    __device__ __forceinline__ void init(const uint32_t *lds_lut) {
+        lut = lds_lut;
+        lane4 = (threadIdx.x & 31u) << 2;
+    }
+    __device__ __forceinline__ void prep_x(uint32_t (&)[8]) const {}
+    template <int NW, int RPL>
+    __device__ __forceinline__ void run_tile(const uint32_t (&w)[NW], const uint32_t (&x)[8],
+                                             float (&acc)[RPL]) const {
+        uint32_t v[RPL][16];
+        hyb1_row_values<K>(w, 0, lut, lane4, v[0]);
+#pragma unroll
+        for (int rr = 0; rr < RPL; rr++) {
+            if (rr + 1 < RPL) hyb1_row_values<K>(w, rr + 1, lut, lane4, v[rr + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < 8; c++)
+                acc[rr] = __builtin_amdgcn_fdot2(as_half2(hyb1_pair(v[rr][2 * c], v[rr][2 * c + 1])),
+                                                 as_half2(x[c]), acc[rr], false);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 };

@@ -30,13 +30,17 @@ float half_bits_to_float(uint16_t h) {
     return (float)v;
 }
 
-// The codes on the host (Algorithms 1-3; code 4: a stored table), values as float.
+// The codes on the host (Algorithms 1-3; code 4: a stored table; code 5: Algorithm 3 at
+// V = 1), values as float.
 void build_codebook(int L, int V, int code_id, const uint16_t *lut, std::vector<float> &C) {
     const int NS = 1 << L;
     C.resize((size_t)NS * V);
     for (uint32_t x = 0; x < (uint32_t)NS; x++) {
         if (code_id == 4) {
             C[x] = half_bits_to_float(lut[x]);
+        } else if (code_id == 5) {  // Algorithm 3 with one entry per row, Q = 6
+            uint32_t X = x * x + x;
+            C[x] = half_bits_to_float((uint16_t)(lut[(X >> 9) & 63u] ^ (X & 0x8000u)));
         } else if (code_id == 0) {
             uint32_t X = x * 34038481u + 76625530u;
             int s = (int)(X & 255u) + (int)((X >> 8) & 255u) + (int)((X >> 16) & 255u) + (int)(X >> 24);

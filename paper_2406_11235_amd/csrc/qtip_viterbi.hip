@@ -169,6 +169,8 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
         } else {
             if constexpr (CODE == CODE_LUT)
                 cpk[r >> 1][r & 1] = reinterpret_cast<const half_t *>(lut)[y];
+            else if constexpr (CODE == CODE_HYB1)
+                cpk[r >> 1][r & 1] = code_hyb1(y, reinterpret_cast<const uint16_t *>(lut));
             else
                 cpk[r >> 1][r & 1] = CODE == CODE_3INST ? code_3inst(y) : code_1mad(y);
         }
@@ -518,7 +520,11 @@ size_t quantize_gpu_workspace(int k, int V, long tiles) {
 hipError_t launch_quantize_gpu(int k, int code_id, const float *W, int m, int n, int ld, const uint32_t *lut,
                                uint32_t *codes, float *tile_err, void *ws, size_t ws_bytes,
                                hipStream_t st) {
-    if (code_id == CODE_LUT) {
+    if (code_id == CODE_HYB1) {
+        if (k == 2) return quantize_gpu_t<2, 1, CODE_HYB1>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        if (k == 3) return quantize_gpu_t<3, 1, CODE_HYB1>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+        return quantize_gpu_t<4, 1, CODE_HYB1>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
+    } else if (code_id == CODE_LUT) {
         if (k == 2) return quantize_gpu_t<2, 1, CODE_LUT>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
         if (k == 3) return quantize_gpu_t<3, 1, CODE_LUT>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);
         return quantize_gpu_t<4, 1, CODE_LUT>(W, m, n, ld, lut, codes, tile_err, ws, ws_bytes, st);

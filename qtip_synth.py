@@ -11,15 +11,17 @@ random bits); no model weights or datasets are used.
 Recipe: numpy.random.Generator(PCG64(240611235 + 1000*config + subcase)),
 drawn in this order: code words (uniform uint32), signs_n, signs_m (+1/-1 int8,
 P = 1/2), row scale (fp16 of U(0.5, 1.5), only where the workload has one),
-LUT (fp16 of N(0,1), shape 512x2 for HYB, 2^14 values for the lookup-only code), X (fp16 of N(0,1),
+LUT (fp16 of N(0,1), shape 512x2 for HYB, 2^14 values for the lookup-only code, 64 for the V = 1
+hash code), X (fp16 of N(0,1),
 shape B x n).
 """
 from dataclasses import dataclass, replace
 
 import numpy as np
 
-CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT = 0, 1, 2, 3, 4
-CODE_NAMES = {CODE_1MAD: "1MAD", CODE_3INST: "3INST", CODE_HYB: "HYB", CODE_HYB2: "HYB2", CODE_LUT: "LUT14"}
+CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT, CODE_HYB1 = 0, 1, 2, 3, 4, 5
+CODE_NAMES = {CODE_1MAD: "1MAD", CODE_3INST: "3INST", CODE_HYB: "HYB", CODE_HYB2: "HYB2", CODE_LUT: "LUT14",
+              CODE_HYB1: "HYB1"}
 BASE_SEED = 240611235
 
 
@@ -80,6 +82,7 @@ WORKLOADS = {w.name: w for w in [
     _w("cfg4_hyb_k2_8192x28672", 4, 0, 8192, 28672, CODE_HYB, 2, 2, 4096, 4096),
     _w("next_hyb2_k2_8192x28672", 6, 0, 8192, 28672, CODE_HYB2, 2, 2, 4096, 4096),
     _w("next_lut14_k2_8192x28672", 7, 0, 8192, 28672, CODE_LUT, 2, 1, 4096, 4096, L=14),
+    _w("next_hyb1_k2_8192x28672", 8, 0, 8192, 28672, CODE_HYB1, 2, 1, 4096, 4096, Q=6),
     _w("cfg5_hyb_k4_8192x8192_b1", 5, 0, 8192, 8192, CODE_HYB, 4, 2, 4096, 4096, B=1),
     _w("cfg5_hyb_k4_8192x8192_b4", 5, 1, 8192, 8192, CODE_HYB, 4, 2, 4096, 4096, B=4),
     _w("cfg5_hyb_k4_8192x8192_b16", 5, 2, 8192, 8192, CODE_HYB, 4, 2, 4096, 4096, B=16),
@@ -101,7 +104,7 @@ class Inputs:
     signs_n: np.ndarray     # int8 +1/-1, (n,)
     signs_m: np.ndarray     # int8 +1/-1, (m,)
     row_scale: np.ndarray   # float16 (m,) or None
-    lut: np.ndarray         # float16 (512, 2), (2^14,) or None
+    lut: np.ndarray         # float16 (512, 2), (2^14,), (64,) or None
     X: np.ndarray           # float16 (B, n)
 
 
@@ -119,5 +122,7 @@ def make_inputs(w, seed=None):
         lut = rng.standard_normal(size=(1 << w.Q, 2)).astype(np.float16)
     elif w.code_id == CODE_LUT:
         lut = rng.standard_normal(size=1 << w.L).astype(np.float16)
+    elif w.code_id == CODE_HYB1:
+        lut = rng.standard_normal(size=64).astype(np.float16)
     X = rng.standard_normal(size=(w.B, w.n)).astype(np.float16)
     return Inputs(codes, signs_n, signs_m, row_scale, lut, X)

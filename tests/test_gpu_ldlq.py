@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
-from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2
+from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB1, CODE_HYB2
 
 pytestmark = pytest.mark.gpu
 
@@ -78,10 +78,13 @@ def test_block_ldl_matches_the_oracle(q, n):
     assert np.allclose(Lg @ Dfull @ Lg.T, H, rtol=1e-5, atol=1e-6)
 
 
-@pytest.mark.parametrize("code_id,k,V", [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 2, 2), (CODE_HYB2, 2, 2)])
+@pytest.mark.parametrize("code_id,k,V", [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 2, 2), (CODE_HYB2, 2, 2),
+                                          (CODE_HYB1, 2, 1)])
 def test_ldlq_streams_equal_the_oracle_loop(q, code_id, k, V):
     rng = np.random.default_rng(700 + 10 * code_id + k)
     lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id in (CODE_HYB, CODE_HYB2) else None
+    if code_id == CODE_HYB1:
+        lut = rng.standard_normal(64).astype(np.float16)
     C = oracle.codebook(16, V, code_id, lut)
     m, n = 32, 64
     W = (rng.standard_normal((m, n)) * C.std()).astype(np.float32)

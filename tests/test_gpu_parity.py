@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 import qtip_synth as synth
-from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2
+from qtip_synth import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB1, CODE_HYB2
 
 pytestmark = pytest.mark.gpu
 
@@ -63,7 +63,8 @@ def run_matmat(q, w, inp, use_matvec=False, scale=True):
 ALL_CODECS = [(CODE_3INST, 2, 1), (CODE_3INST, 3, 1), (CODE_3INST, 4, 1),
               (CODE_1MAD, 2, 1), (CODE_1MAD, 3, 1), (CODE_1MAD, 4, 1),
               (CODE_HYB, 2, 2), (CODE_HYB, 3, 2), (CODE_HYB, 4, 2),
-              (CODE_HYB2, 2, 2), (CODE_HYB2, 3, 2), (CODE_HYB2, 4, 2)]
+              (CODE_HYB2, 2, 2), (CODE_HYB2, 3, 2), (CODE_HYB2, 4, 2),
+              (CODE_HYB1, 2, 1), (CODE_HYB1, 3, 1), (CODE_HYB1, 4, 1)]
 
 
 def small_workload(code_id, k, V, m, n, B=1, row_scale=False, sub=0):
@@ -74,11 +75,13 @@ def small_workload(code_id, k, V, m, n, B=1, row_scale=False, sub=0):
 
 # ------------------------------------------------------------------ the codes
 
-@pytest.mark.parametrize("code_id,V", [(CODE_1MAD, 1), (CODE_3INST, 1), (CODE_HYB, 2), (CODE_HYB2, 2)])
+@pytest.mark.parametrize("code_id,V", [(CODE_1MAD, 1), (CODE_3INST, 1), (CODE_HYB, 2), (CODE_HYB2, 2), (CODE_HYB1, 1)])
 def test_code_table_all_states_bit_exact(q, code_id, V):
     import torch
     rng = np.random.default_rng(42)
     lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id in (CODE_HYB, CODE_HYB2) else None
+    if code_id == CODE_HYB1:
+        lut = rng.standard_normal(64).astype(np.float16)
     states = np.arange(65536, dtype=np.uint32)
     out = torch.zeros(65536 * V, dtype=torch.float16, device="cuda")
     q.qtip_decode_states(dev(states), 65536, 16, V, code_id, dev(lut), out)
@@ -189,7 +192,8 @@ FULL = ["cfg1_3inst_k2_1024x1024", "cfg2_3inst_k2_4096x4096", "cfg3_1mad_k2_1433
         "cfg3_1mad_k3_14336x4096", "cfg3_1mad_k4_14336x4096", "cfg3_1mad_k2_4096x14336",
         "cfg3_1mad_k3_4096x14336", "cfg3_1mad_k4_4096x14336", "cfg4_hyb_k2_8192x28672",
         "cfg5_hyb_k4_8192x8192_b1", "cfg5_hyb_k4_8192x8192_b4", "cfg5_hyb_k4_8192x8192_b16",
-        "cfg5_hyb_k4_8192x8192_b64", "metric_3inst_k2_8192x28672", "next_hyb2_k2_8192x28672"]
+        "cfg5_hyb_k4_8192x8192_b64", "metric_3inst_k2_8192x28672", "next_hyb2_k2_8192x28672",
+        "next_hyb1_k2_8192x28672"]
 
 
 def sample_rows(w, rng, count=48):

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT
+from oracle import CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB1, CODE_HYB2, CODE_LUT
 
 
 @pytest.fixture(scope="module")
@@ -18,10 +18,13 @@ def q():
 
 
 @pytest.mark.parametrize("code_id,k,V", [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_1MAD, 4, 1),
-                                          (CODE_HYB, 2, 2), (CODE_HYB, 4, 2), (CODE_HYB2, 2, 2)])
+                                          (CODE_HYB, 2, 2), (CODE_HYB, 4, 2), (CODE_HYB2, 2, 2),
+                                          (CODE_HYB1, 2, 1)])
 def test_quantizer_matches_oracle_algorithm4(q, code_id, k, V):
     rng = np.random.default_rng(100 + 10 * code_id + k)
     lut = rng.standard_normal((512, 2)).astype(np.float16) if code_id in (CODE_HYB, CODE_HYB2) else None
+    if code_id == CODE_HYB1:
+        lut = rng.standard_normal(64).astype(np.float16)
     C = oracle.codebook(16, V, code_id, lut)
     sd = C.std()
     m, n = 16, 32
