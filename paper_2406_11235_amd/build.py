@@ -23,16 +23,32 @@ def is_stale():
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force=True, extra_flags=(), verbose=False, out=None):
-    """Compile every source into paper_2406_11235_amd/libqtip.so (or `out`)."""
+def build(force=True, extra_flags=(), verbose=False, out=None, jobs=None):
+    """Compile every source into paper_2406_11235_amd/libqtip.so (or `out`): one hipcc
+    process per source file, a few at a time, then one link."""
     if out is None and not force and not is_stale():
         return LIB
+    import concurrent.futures
+    import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra_flags) + ["-x", "hip"] + \
-          [os.path.join(CSRC, f) for f in SOURCES] + ["-o", out or LIB]
-    if verbose:
-        print(" ".join(cmd), file=sys.stderr)
-    subprocess.run(cmd, check=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"] + list(extra_flags)
+    jobs = jobs or min(len(SOURCES), max(1, (os.cpu_count() or 2) - 1))
+    scratch = os.path.join(HERE, "_build")  # object files only; removed again below
+    os.makedirs(scratch, exist_ok=True)
+    with tempfile.TemporaryDirectory(prefix="obj_", dir=scratch) as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, os.path.splitext(src)[0] + ".o")
+            cmd = [hipcc] + compile_flags + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), file=sys.stderr)
+            subprocess.run(cmd, check=True)
+            return obj
+        with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread"] + objs + ["-o", out or LIB]
+        if verbose:
+            print(" ".join(link), file=sys.stderr)
+        subprocess.run(link, check=True)
     return out or LIB
 
 
