@@ -75,7 +75,7 @@ extern "C" {
 #define QTIP_CODE_HYB2 3  /* the same with bit 31 of the hash also XORed (Section 3.1.2): the first
                              entry gets a sign of its own; for L = 16 that bit is set exactly when
                              the state is at least 46341 */
-#define QTIP_CODE_HYB1 5  /* Algorithm 3 with one entry per row: L = 16, V = 1, Q = 6 (Section 4.2's remark
+#define QTIP_CODE_HYB1 5  /* Algorithm 3 with one entry per row: L = 16, V = 1, Q = 6 (Section 4.3's remark
                              on hardware with a 64-entry table lookup): bits 9..14 of the hash index
                              64 fp16 values, bit 15 negates the value */
 #define QTIP_CODE_LUT 4   /* lookup-only code (appendix on lookup-only codes): L = 14, V = 1, the value

@@ -55,7 +55,7 @@
 #define ORC_CODE_HYB 2
 #define ORC_CODE_HYB2 3
 #define ORC_CODE_LUT 4 /* lookup-only: the value of a state is table entry [state] */
-#define ORC_CODE_HYB1 5 /* Algorithm 3 with V = 1 (the Q = 6 one-dimensional table of Section 4.2's remark) */
+#define ORC_CODE_HYB1 5 /* Algorithm 3 with V = 1 (the Q = 6 one-dimensional table of Section 4.3's remark) */
 
 int orc_threads(void) {
 #ifdef _OPENMP
