@@ -123,8 +123,13 @@ __global__ void decode_states_kernel(const uint32_t *__restrict__ states, int co
 // of the stand-alone transform, so that the result is the same bit for bit.
 constexpr int FUSED_MAX_N = 8192;
 
-template <int K, int V, int CODE, int NW, bool FUSED>
-__global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restrict__ codes,
+// SPREAD: the HYB codes' table in 16 copies (see RowDotHyb); it costs 64 KiB of LDS and their
+// filling per workgroup, and pays on long rows.  (Eight waves per SIMD, i.e. at most 64
+// registers: the loop needs no more, and a second workgroup per CU is worth more than the few
+// values that spill around it.)
+// (The V = 1 hash code keeps a whole tile's table reads in flight and needs more registers.)
+template <int K, int V, int CODE, int NW, bool FUSED, bool SPREAD = false>
+__global__ __launch_bounds__(NW * 64, CODE == CODE_HYB1 ? 4 : 8) void matvec_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
                                                          int tn, const half_t *__restrict__ x,
                                                          const int8_t *__restrict__ signs, int log2_block,
@@ -132,7 +137,7 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
                                                          float *__restrict__ y) {
     constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
     constexpr int TPI = 64 / LPT;  // tiles per wave per iteration
-    __shared__ uint32_t s_lut[code_lds_words(CODE)];
+    __shared__ __attribute__((aligned(16))) uint32_t s_lut[code_lds_words(CODE, SPREAD)];
     __shared__ float s_part[NW][16];
     __shared__ __attribute__((aligned(16))) half_t s_x[FUSED ? FUSED_MAX_N : 8];
     // room for FUSED_MAX_N values in blocks of any size, each block with its padding
@@ -152,8 +157,8 @@ __global__ __launch_bounds__(NW * 64) void matvec_kernel(const uint32_t *__restr
                                  [dst](int idx, half_t v) { dst[idx] = v; });
         }
     }
-    stage_code_table<CODE>(lut, s_lut, NW * 64);
-    RowDot<K, CODE> rd;
+    stage_code_table<CODE, SPREAD>(lut, s_lut, NW * 64);
+    typename RowDotFor<K, CODE, SPREAD>::type rd;
     rd.init(s_lut);
     const int I = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -465,6 +470,15 @@ static int pick_matvec_waves(int tm, int steps_per_row) {
     return 2;
 }
 
+// The 16-copy HYB table: from which row length on it pays for the 64 KiB each workgroup fills
+// (measured: 8192 x 28672 29.9 -> 22.5 us at k = 2, 8192 x 8192 10.0 -> 9.6, 14336 x 4096 10.0 ->
+// 12.0).  The two-sign-flip form is bound by its vector instructions and gains nothing.
+static bool pick_hyb_spread(int code, int n) {
+    static const char *env = getenv("QTIP_HYB_SPREAD");  // tuning override: 0 or 1
+    if (env) return atoi(env) != 0;
+    return code == CODE_HYB && n >= 8192;
+}
+
 template <int K, int V, int CODE>
 static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, int m, int n,
                                   const void *x, const int8_t *signs, int log2_block, const void *scale,
@@ -472,14 +486,18 @@ static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, in
     constexpr int TPI = 64 / Geo<K>::LPT;
     const int tm = m / 16, tn = n / 16;
     const int nw = pick_matvec_waves(tm, (tn + TPI - 1) / TPI);
+    const bool spread = pick_hyb_spread(CODE, n);
     // signs != null: x is untransformed and the kernel transforms it itself (n <= FUSED_MAX_N)
-#define QTIP_MV_LAUNCH(NW)                                                                              \
-    if (signs)                                                                                          \
-        hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW, true>), dim3(tm), dim3(NW * 64), 0, st, codes, \
-                           lut, tn, (const half_t *)x, signs, log2_block, (const half_t *)scale, y);     \
-    else                                                                                                \
-        hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW, false>), dim3(tm), dim3(NW * 64), 0, st,       \
-                           codes, lut, tn, (const half_t *)x, signs, log2_block, (const half_t *)scale, y)
+#define QTIP_MV_LAUNCH3(NW, FUSED, SPREAD)                                                                 \
+    hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW, FUSED, SPREAD>), dim3(tm), dim3(NW * 64), 0, st, codes, \
+                       lut, tn, (const half_t *)x, signs, log2_block, (const half_t *)scale, y)
+#define QTIP_MV_LAUNCH(NW)                                \
+    if (signs)                                            \
+        QTIP_MV_LAUNCH3(NW, true, false);                 \
+    else if (code_is_hyb(CODE) && spread)                 \
+        QTIP_MV_LAUNCH3(NW, false, code_is_hyb(CODE));    \
+    else                                                  \
+        QTIP_MV_LAUNCH3(NW, false, false)
     switch (nw) {
         case 2: QTIP_MV_LAUNCH(2); break;
         case 4: QTIP_MV_LAUNCH(4); break;
@@ -487,6 +505,7 @@ static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, in
         default: QTIP_MV_LAUNCH(8); break;
     }
 #undef QTIP_MV_LAUNCH
+#undef QTIP_MV_LAUNCH3
     return hipGetLastError();
 }
 

@@ -38,9 +38,11 @@ constexpr int CODE_HYB1 = 5;  // Algorithm 3 with one entry per row: V = 1, Q = 
 __host__ __device__ constexpr int code_state_bits(int code) { return code == CODE_LUT ? 14 : 16; }
 __host__ __device__ constexpr int code_log2_ty(int code) { return code == CODE_LUT ? 3 : 4; }
 __host__ __device__ constexpr bool code_is_hyb(int code) { return code == CODE_HYB || code == CODE_HYB2; }
-// words of LDS the hot loops of a code keep their table in (see stage_code_table)
-__host__ __device__ constexpr int code_lds_words(int code) {
-    return code_is_hyb(code) ? 1024 : code == CODE_HYB1 ? 4096 : 1;
+// words of LDS the hot loops of a code keep their table in (see stage_code_table); SPREAD:
+// the batch-1 kernel's form of the HYB table, HYB_SPREAD copies (see RowDotHyb)
+constexpr int HYB_SPREAD = 16;
+__host__ __device__ constexpr int code_lds_words(int code, bool spread = false) {
+    return code_is_hyb(code) ? (spread ? 1024 * HYB_SPREAD : 1024) : code == CODE_HYB1 ? 4096 : 1;
 }
 
 // Section 3.1.1 constants.
@@ -230,10 +232,26 @@ __device__ __forceinline__ void stage_hyb1_table(const uint32_t *__restrict__ lu
         s_lut[i] = v | (v << 16);
     }
 }
-template <int CODE>
+// The same 1024 signed vectors, HYB_SPREAD = 16 copies: word e * 16 + c is vector e for the
+// lanes with lane % 16 == c.  A read of 32 lanes then puts at most two lanes on any bank
+// (lanes l and l + 16, when their vectors' numbers have the same parity), against the
+// three to four that land on the fullest bank when 32 random reads share one copy.  (32
+// copies would leave no conflicts at all but fill 128 KiB, one workgroup per CU instead of
+// two: measured 31.5 us against 22.3 us for 16 copies and 29.9 us for one, 8192 x 28672.)
+__device__ __forceinline__ void stage_signed_lut_spread(const uint32_t *__restrict__ lut, uint32_t *s_lut,
+                                                        int nthreads) {
+    for (int e = threadIdx.x; e < 1024; e += nthreads) {
+        const uint32_t v = lut[e & 511] ^ ((e & 512) ? 0x80000000u : 0u);
+        uint4 *dst = reinterpret_cast<uint4 *>(s_lut + e * HYB_SPREAD);
+#pragma unroll
+        for (int q = 0; q < HYB_SPREAD / 4; q++) dst[q] = uint4{v, v, v, v};
+    }
+}
+template <int CODE, bool SPREAD = false>
 __device__ __forceinline__ void stage_code_table(const uint32_t *__restrict__ lut, uint32_t *s_lut,
                                                  int nthreads) {
-    if constexpr (code_is_hyb(CODE)) stage_signed_lut(lut, s_lut, nthreads);
+    if constexpr (code_is_hyb(CODE) && SPREAD) stage_signed_lut_spread(lut, s_lut, nthreads);
+    if constexpr (code_is_hyb(CODE) && !SPREAD) stage_signed_lut(lut, s_lut, nthreads);
     if constexpr (CODE == CODE_HYB1) stage_hyb1_table(lut, s_lut, nthreads);
     if constexpr (code_lds_words(CODE) > 1) __syncthreads();
 }
@@ -450,9 +468,20 @@ template <int K> struct RowDot<K, CODE_1MAD> {
 // same way); the hot loop reads that 4 KiB table from LDS, built by the kernel from the
 // 512 stored rows: signed[s * 512 + idx] = row idx with entry 1 negated iff s.  One
 // shift and one mask turn a hash into a byte address, and no sign fix-up is left.
-template <int K, bool TWO> struct RowDotHyb {
+// SPREAD: the table holds HYB_SPREAD copies of every vector (stage_signed_lut_spread) and a
+// lane reads its own; else one copy (stage_signed_lut).
+template <int K, bool TWO, bool SPREAD> struct RowDotHyb {
     const uint32_t *lut;  // LDS: the 1024 signed vectors
-    __device__ __forceinline__ void init(const uint32_t *lds_lut) { lut = lds_lut; }
+    uint32_t lane4;       // SPREAD: byte offset of this lane's copy inside a vector's 64 bytes
+    __device__ __forceinline__ void init(const uint32_t *lds_lut) {
+        lut = lds_lut;
+        lane4 = (threadIdx.x & (HYB_SPREAD - 1)) << 2;
+    }
+    // byte address of the vector selected by hash bits 6..15, given those bits at 6..15 of h
+    __device__ __forceinline__ uint32_t address(uint32_t h) const {
+        if constexpr (SPREAD) return (h & 0xFFC0u) | lane4;  // times 64 bytes: in place already
+        else return (h >> 4) & 0xFFCu;
+    }
     __device__ __forceinline__ void prep_x(uint32_t (&)[8]) const {}
     // All RPL rows of this lane, software-pipelined by row: the hashes and the eight
     // table reads of row r+1 are issued before the reads of row r are consumed, so
@@ -474,9 +503,10 @@ template <int K, bool TWO> struct RowDotHyb {
                         // both hashes at once: low 16 bits of x*x + x in each half
                         uint32_t H;
                         asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H) : "v"(R));
-                        // hash bits 6..15 -> byte address; state base+j sits in the high half
-                        v[rr][base + j] = hyb_signed_lookup(lut, (H >> 20) & 0xFFCu);
-                        v[rr][base + j + G] = hyb_signed_lookup(lut, (H >> 4) & 0xFFCu);
+                        // hash bits 6..15 times 64 bytes (they are in place already) plus this
+                        // lane's copy; state base+j sits in the high half
+                        v[rr][base + j] = hyb_signed_lookup(lut, address(H >> 16));
+                        v[rr][base + j + G] = hyb_signed_lookup(lut, address(H));
                         if constexpr (TWO) {  // TWO: the first entry's sign, from the states themselves
                             const uint32_t M = hyb2_sign_mask(R);
                             v[rr][base + j] ^= M >> 16;
@@ -501,7 +531,7 @@ template <int K, bool TWO> struct RowDotHyb {
                 for (int c = 0; c < 8; c++) {
                     const uint32_t st = window16(w, rr * 16 * K + c * 2 * K);
                     const uint32_t X = st * st + st;
-                    uint32_t v = hyb_signed_lookup(lut, (X >> 4) & 0xFFCu);
+                    uint32_t v = hyb_signed_lookup(lut, address(X));
                     if constexpr (TWO) v ^= (X >> 16) & 0x8000u;
                     acc[rr] = __builtin_amdgcn_fdot2(as_half2(v), as_half2(x[c]), acc[rr], false);
                 }
@@ -534,7 +564,11 @@ template <int K> struct RowDot<K, CODE_HYB1> {
         }
     }
 };
-template <int K> struct RowDot<K, CODE_HYB> : RowDotHyb<K, false> {};
-template <int K> struct RowDot<K, CODE_HYB2> : RowDotHyb<K, true> {};
+template <int K> struct RowDot<K, CODE_HYB> : RowDotHyb<K, false, false> {};
+template <int K> struct RowDot<K, CODE_HYB2> : RowDotHyb<K, true, false> {};
+// The batch-1 kernel's choice: the spread table for the HYB codes when it asks for it.
+template <int K, int CODE, bool SPREAD> struct RowDotFor { using type = RowDot<K, CODE>; };
+template <int K> struct RowDotFor<K, CODE_HYB, true> { using type = RowDotHyb<K, false, true>; };
+template <int K> struct RowDotFor<K, CODE_HYB2, true> { using type = RowDotHyb<K, true, true>; };
 
 }  // namespace qtip
