@@ -276,7 +276,9 @@ __device__ __forceinline__ void align_row_words(int i, uint32_t (&w)[3]) {
     }
 }
 
-template <int K, int V, int CODE, int NB, int NW, bool STAGE>
+// SPREAD: the HYB table in 16 copies, as in the batch-1 kernel (64 KiB: only next to the
+// small partial-sum buffer of NB = 1).
+template <int K, int V, int CODE, int NB, int NW, bool STAGE, bool SPREAD = false>
 __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
                                                          int tm, int tn, const half_t *__restrict__ X,
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
                                                          float *__restrict__ Y) {
     constexpr int R = 2;
     constexpr int NWORDS = 8 * K;
-    __shared__ uint32_t s_lut[code_lds_words(CODE)];
+    __shared__ __attribute__((aligned(16))) uint32_t s_lut[code_lds_words(CODE, SPREAD)];
     // one buffer, used twice: in the loop each wave's staging region (SR batch rows at a
     // time, 128 bytes each, padded to 144 so that the row-wise writes and the
     // column-wise reads both spread over the banks), after it the partial sums
@@ -293,8 +295,8 @@ __global__ __launch_bounds__(NW * 64) void matmat_kernel(const uint32_t *__restr
     constexpr int STAGE_FLOATS = STAGE ? NW * SR * XST / 4 : 0;
     __shared__ __attribute__((aligned(16))) float s_buf[PART_FLOATS > STAGE_FLOATS ? PART_FLOATS : STAGE_FLOATS];
     float(*s_part)[R][NB][4][64] = reinterpret_cast<float(*)[R][NB][4][64]>(s_buf);
-    stage_code_table<CODE>(lut, s_lut, NW * 64);
-    RowDecode<K, CODE> rdec;
+    stage_code_table<CODE, SPREAD>(lut, s_lut, NW * 64);
+    RowDecode<K, CODE, SPREAD> rdec;
     rdec.init(s_lut);
     const int I0 = blockIdx.x * R;
     const int b0 = blockIdx.y * (16 * NB);
@@ -518,12 +520,20 @@ static hipError_t launch_matmat_t(const uint32_t *codes, const uint32_t *lut, in
     const int tm = m / 16, tn = n / 16;
     const dim3 block(NW * 64);
     const half_t *Xh = (const half_t *)X, *sc = (const half_t *)scale;
+    constexpr bool HYB = CODE == CODE_HYB;
+    // (measured: the 16 table copies pay at 9 to 16 batch rows, 8192 x 8192 13.1 -> 12.3 us and
+    // 8192 x 28672 35 -> 31 us, and make no difference below)
+    const bool spread = HYB && pick_hyb_spread(CODE, n);
     if (groups == 1 && B <= 8) {  // few distinct batch rows: load the B operand directly
         hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW, false>), dim3((tm + 1) / 2, 1), block, 0,
                            st, codes, lut, tm, tn, Xh, B, sc, Y);
     } else if (groups == 1) {
-        hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW, true>), dim3((tm + 1) / 2, 1), block, 0,
-                           st, codes, lut, tm, tn, Xh, B, sc, Y);
+        if (spread)
+            hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW, true, HYB>), dim3((tm + 1) / 2, 1), block, 0,
+                               st, codes, lut, tm, tn, Xh, B, sc, Y);
+        else
+            hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 1, NW, true>), dim3((tm + 1) / 2, 1), block, 0,
+                               st, codes, lut, tm, tn, Xh, B, sc, Y);
     } else if (groups == 2) {
         hipLaunchKernelGGL((matmat_kernel<K, V, CODE, 2, NW, true>), dim3((tm + 1) / 2, 1), block, 0,
                            st, codes, lut, tm, tn, Xh, B, sc, Y);

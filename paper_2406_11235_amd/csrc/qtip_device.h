@@ -317,10 +317,16 @@ __device__ __forceinline__ void dot2x2_tail(uint32_t p, uint32_t q, uint32_t xa,
 // One tile row decoded to 8 packed fp16 pairs in column order, with the hot-loop
 // instruction sequences (same bits as the plain code functions).  Used where the
 // weights feed the matrix cores.
-template <int K, int CODE> struct RowDecode {
+// SPREAD (HYB only): the table holds HYB_SPREAD copies of every vector, as in RowDotHyb.
+template <int K, int CODE, bool SPREAD = false> struct RowDecode {
     uint64_t b64;
     uint32_t mm;
     const uint32_t *lut;
+    // byte address of the HYB vector selected by hash bits 6..15, given at bits 6..15 of h
+    __device__ __forceinline__ uint32_t hyb_address(uint32_t h) const {
+        if constexpr (SPREAD) return (h & 0xFFC0u) | ((threadIdx.x & (HYB_SPREAD - 1)) << 2);
+        else return (h >> 4) & 0xFFCu;
+    }
     __device__ __forceinline__ void init(const uint32_t *lds_lut) {
         lut = lds_lut;
         b64 = CODE == CODE_3INST ? INST_B : MAD_B;
@@ -368,8 +374,8 @@ template <int K, int CODE> struct RowDecode {
                         uint32_t H;
                         asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(H) : "v"(R));
                         // state base+j in the high half of H, state base+j+G in the low half
-                        h[base + j] = hyb_signed_lookup(lut, (H >> 20) & 0xFFCu);
-                        h[base + j + G] = hyb_signed_lookup(lut, (H >> 4) & 0xFFCu);
+                        h[base + j] = hyb_signed_lookup(lut, hyb_address(H >> 16));
+                        h[base + j + G] = hyb_signed_lookup(lut, hyb_address(H));
                         if constexpr (CODE == CODE_HYB2) {
                             const uint32_t M = hyb2_sign_mask(R);
                             h[base + j] ^= M >> 16;
@@ -381,7 +387,7 @@ template <int K, int CODE> struct RowDecode {
                 for (int c = 0; c < 8; c++) {
                     const uint32_t st = window16(w, P0 + c * 2 * K);
                     const uint32_t X = st * st + st;
-                    h[c] = hyb_signed_lookup(lut, (X >> 4) & 0xFFCu);
+                    h[c] = hyb_signed_lookup(lut, hyb_address(X));
                     if constexpr (CODE == CODE_HYB2) h[c] ^= (X >> 16) & 0x8000u;
                 }
             }
