@@ -304,6 +304,140 @@ __global__ __launch_bounds__(NW * 64) void lut_matmat_kernel(const uint32_t *__r
     }
 }
 
+// The same for more than 16 batch rows.  The B operand puts neighbouring lanes on different
+// batch rows, i.e. different cache lines, which the texture path serves at a fraction of the
+// rate of a load whose neighbouring lanes read neighbouring addresses.  Here a wave loads its
+// activations line by line instead, for four steps at once (8 lanes = the 128 bytes one
+// batch row has under eight blocks), and transposes them through a private piece of LDS, as
+// the 16 x 16 kernel does.
+template <int K, int NB, int NW>
+__global__ __launch_bounds__(NW * 64) void lut_matmat_staged_kernel(const uint32_t *__restrict__ codes,
+                                                                    const uint16_t *__restrict__ lut, int tn,
+                                                                    int m, const half_t *__restrict__ X, int B,
+                                                                    const half_t *__restrict__ scale,
+                                                                    float *__restrict__ Y) {
+    constexpr int NWORDS = 8 * K;
+    constexpr int ROWS = 32 * NB, NQ = ROWS / 8, XST = 144;  // rows padded to 144 bytes (banks)
+    constexpr int PART_BYTES = (NW - 1) * NB * 16 * 64 * 4, STAGE_BYTES = NW * ROWS * XST;
+    __shared__ __attribute__((aligned(16))) uint16_t s_tab[LUT_STATES];
+    // one buffer, used twice: the waves' staging regions in the loop, the partial sums after it
+    __shared__ __attribute__((aligned(16))) char s_buf[PART_BYTES > STAGE_BYTES ? PART_BYTES : STAGE_BYTES];
+    float(*s_part)[NB][16][64] = reinterpret_cast<float(*)[NB][16][64]>(s_buf);
+    stage_table(lut, s_tab, NW * 64);
+    __syncthreads();
+    const int I = blockIdx.x;
+    const int b0 = blockIdx.y * ROWS;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int i = lane & 31, s = lane >> 5;
+    const int lr = lane >> 3, ch = lane & 7;
+    char *const stage = s_buf + wave * (ROWS * XST);
+    const size_t n = (size_t)tn * LUT_TY;
+    const int chunk = ((tn + NW * 8 - 1) / (NW * 8)) * 8;
+    const int J0 = wave * chunk;
+    const int Jend = min(tn, J0 + chunk);
+    const int bit = 8 * K * i, w0 = bit >> 5, sh = bit & 31;
+
+    float16_t acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[nb][e] = 0.f;
+
+    uint32_t wn[2];
+    half8_t xq[NQ];  // piece ch of batch rows b0 + 8 q + lr, for the eight blocks from Jm on
+    auto load_x = [&](int Jm) {
+        const int Jx = min(Jm + ch, Jend - 1);
+#pragma unroll
+        for (int q = 0; q < NQ; q++) {
+            const int b = b0 + 8 * q + lr;
+            xq[q] = *reinterpret_cast<const half8_t *>(X + (size_t)min(b, B - 1) * n + LUT_TY * Jx);
+        }
+    };
+    auto issue_w = [&](int Jb) {
+        const int J = min(Jb + s, Jend - 1);  // a half past the end re-reads the last block
+        const uint32_t *tile = codes + ((size_t)I * tn + J) * NWORDS;
+        wn[0] = tile[w0];
+        wn[1] = tile[(w0 + 1) % NWORDS];  // wraps inside the block (tail-biting)
+    };
+    auto decode = [&](half8_t &a) {
+        const uint64_t both = (((uint64_t)wn[0] << 32) | wn[1]) << sh;
+        const uint32_t w[2] = {(uint32_t)(both >> 32), (uint32_t)both};
+#pragma unroll
+        for (int c = 0; c < 8; c++) a[c] = table_at(s_tab, table_offset(w, c * K));
+    };
+    auto wave_sync = [] {  // the LDS operations of one wave complete in order; keep the compiler in line
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    half8_t a1;
+    if (J0 < Jend) {
+        load_x(J0);
+        issue_w(J0);
+        decode(a1);
+        if (J0 + 2 < Jend) issue_w(J0 + 2);
+    }
+    for (int Jm = J0; Jm < Jend; Jm += 8) {
+#pragma unroll
+        for (int q = 0; q < NQ; q++) *reinterpret_cast<half8_t *>(stage + (8 * q + lr) * XST + 16 * ch) = xq[q];
+        wave_sync();
+        if (Jm + 8 < Jend) load_x(Jm + 8);
+#pragma unroll
+        for (int sub = 0; sub < 4; sub++) {
+            const int Jb = Jm + 2 * sub;
+            if (Jb < Jend) {  // the same for the whole wave
+                const half8_t a = a1;
+                const bool live = Jb + s < Jend;
+                half8_t xb[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; nb++) {
+                    xb[nb] = *reinterpret_cast<const half8_t *>(stage + (32 * nb + i) * XST + 16 * (2 * sub + s));
+                    if (!live) xb[nb] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};  // this half has no block
+                }
+                if (Jb + 2 < Jend) {
+                    decode(a1);
+                    if (Jb + 4 < Jend) issue_w(Jb + 4);
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; nb++)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, xb[nb], acc[nb], 0, 0, 0);
+            }
+        }
+        wave_sync();  // all reads of this round before the next round's writes
+    }
+    __syncthreads();  // the staging regions become the partial sums
+    if (wave > 0) {
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) s_part[wave - 1][nb][e][lane] = acc[nb][e];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) {
+            const int b = b0 + 32 * nb + i;
+            if (b >= B) continue;
+#pragma unroll
+            for (int e4 = 0; e4 < 4; e4++) {
+                float4_t v;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    v[e] = acc[nb][4 * e4 + e];
+#pragma unroll
+                    for (int wv = 0; wv < NW - 1; wv++) v[e] += s_part[wv][nb][4 * e4 + e][lane];
+                }
+                const int orow = LUT_TX * I + 8 * e4 + 4 * s;
+                if (scale) {
+#pragma unroll
+                    for (int e = 0; e < 4; e++) v[e] *= (float)scale[orow + e];
+                }
+                *reinterpret_cast<float4_t *>(Y + (size_t)b * m + orow) = v;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ launchers
@@ -360,12 +494,15 @@ static hipError_t lut_matmat_t(const uint32_t *codes, const uint16_t *tab, int m
                                const void *scale, float *Y, hipStream_t st) {
     const int tm = m / LUT_TX, tn = n / LUT_TY;
     // a workgroup owns 32 outputs, so there are few workgroups: many waves each
-    if (B <= 32)
+    if (B <= 16)  // few distinct batch rows: load the B operand directly
         hipLaunchKernelGGL((lut_matmat_kernel<K, 1, 16>), dim3(tm, 1), dim3(1024), 0, st, codes, tab, tn, m,
                            (const half_t *)X, B, (const half_t *)scale, Y);
+    else if (B <= 32)
+        hipLaunchKernelGGL((lut_matmat_staged_kernel<K, 1, 16>), dim3(tm, 1), dim3(1024), 0, st, codes, tab, tn,
+                           m, (const half_t *)X, B, (const half_t *)scale, Y);
     else
-        hipLaunchKernelGGL((lut_matmat_kernel<K, 2, 8>), dim3(tm, (B + 63) / 64), dim3(512), 0, st, codes,
-                           tab, tn, m, (const half_t *)X, B, (const half_t *)scale, Y);
+        hipLaunchKernelGGL((lut_matmat_staged_kernel<K, 2, 8>), dim3(tm, (B + 63) / 64), dim3(512), 0, st,
+                           codes, tab, tn, m, (const half_t *)X, B, (const half_t *)scale, Y);
     return hipGetLastError();
 }
 
