@@ -164,6 +164,24 @@ def test_matmat_large_batch_staged_activations(q, code_id, k, V, m, n, B):
     assert np.array_equal(run_matmat(q, w, inp), got)  # fixed summation order
 
 
+@pytest.mark.parametrize("k", [2, 3, 4])
+@pytest.mark.parametrize("n", [8192, 8208, 16400])
+def test_hyb_long_rows_use_the_spread_table(q, k, n):
+    """From 8192 columns on the HYB kernels read a table held in 16 copies (batch 1, and 9 to 16
+    batch rows on the matrix cores); same weights, so the same bars, and the same bits as the
+    one-copy kernel wherever the summation order is the same (batch 1)."""
+    m = 48
+    for B in (1, 9, 16):
+        w = small_workload(CODE_HYB, k, 2, m, n, B=B, row_scale=B > 1, sub=60 + B)
+        inp = synth.make_inputs(w)
+        Wref = oracle.dequantize(inp.codes, 16, k, 2, CODE_HYB, m, n, inp.lut)
+        ref = oracle.matmat_dense(Wref, inp.X, inp.row_scale)
+        got = run_matmat(q, w, inp)
+        err = rel_err(got, ref)
+        assert err <= REL_TOL and err <= OBSERVED_TOL, (B, err)
+        assert np.array_equal(run_matmat(q, w, inp), got)
+
+
 def test_stacked_matrices_are_one_launch(q):
     """Matrices that share an input (q/k/v, up/gate: the matrix fusion of the paper's
     generation-speed runs) are stacked along the rows: tile rows are independent and contiguous in the code buffer, so the
