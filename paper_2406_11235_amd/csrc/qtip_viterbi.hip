@@ -153,14 +153,20 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
     constexpr int G = VT_T / V;
     constexpr bool HYB = code_is_hyb(CODE);
     constexpr int ROWS = CODE == CODE_HYB2 ? 2048 : 1024;  // signed table rows a state can select
+    // The per-step error table is read at random (one read per state and step), so it is kept
+    // in DCOPY copies: word row * DCOPY + c belongs to the lanes with lane % DCOPY == c, and a
+    // 32-lane pass finds at most four lanes on four banks instead of 32 on 32 (the fullest
+    // bank then holds about 2 reads instead of 3.5).
+    constexpr int DCOPY = 8;
     static_assert(HYB == (V == 2), "V = 2 is the HYB code");
     // LDS: minima (or, for kV = 8, per-thread partial minima, their predecessors and the
     // 256 minima), reused for the final reduction; then the HYB error table
     constexpr int BEST_FLOATS = Geo::LOCAL ? vit_max(NP, 2 * VT_NT) : 2 * VT_NT + NP;
-    __shared__ float s_mem[BEST_FLOATS + VT_T + (HYB ? ROWS : 0)];
+    __shared__ __attribute__((aligned(16))) float s_mem[BEST_FLOATS + VT_T + (HYB ? ROWS * DCOPY : 0)];
     float *const s_best = s_mem;
     float *const s_seq = s_mem + BEST_FLOATS;      // the sequence
     float *const s_D = s_mem + BEST_FLOATS + VT_T;  // HYB only
+    const float *const s_Dmine = s_D + (threadIdx.x & (DCOPY - 1));
 
     const int tid = threadIdx.x;
     const int slot = blockIdx.x;
@@ -197,9 +203,9 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
             if constexpr (CODE == CODE_HYB2) row |= (X >> 31) << 10;  // second sign bit
             // kept as the byte offset of the row's error in the per-step table
             if (r & 1)
-                ipk[r >> 1] |= (row * 4) << 16;
+                ipk[r >> 1] |= (row * 4 * DCOPY) << 16;
             else
-                ipk[r >> 1] = row * 4;
+                ipk[r >> 1] = row * 4 * DCOPY;
         } else {
             if constexpr (CODE == CODE_LUT)
                 cpk[r >> 1][r & 1] = reinterpret_cast<const half_t *>(lut)[y];
@@ -229,6 +235,11 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
         const float e0 = c0 - s0, e1 = c1 - s1;
         return __builtin_fmaf(e1, e1, e0 * e0);
     };
+    auto store_error = [&](int row, float e) {  // all copies of one row: 16-byte stores
+        float4_t *dst = reinterpret_cast<float4_t *>(s_D + row * DCOPY);
+#pragma unroll
+        for (int q = 0; q < DCOPY / 4; q++) dst[q] = float4_t{e, e, e, e};
+    };
     // New values of states 2 r2 and 2 r2 + 1 of this thread (they share a packed register)
     // from the minima b0, b1 of their prefixes: fma(e, e, b) for V = 1, b + table entry for
     // HYB.  The unpacking is pinned here (volatile asm): hoisted out of the step loop it turns
@@ -242,8 +253,9 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
             asm volatile("v_and_b32 %0, 0xffff, %2\n\tv_lshrrev_b32 %1, 16, %2"
                          : "=&v"(o0), "=v"(o1)
                          : "v"(ipk[r2]));
-            v0 = b0 + *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o0);
-            v1 = b1 + *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_D) + o1);
+            // (s_Dmine = the table shifted by this lane's copy)
+            v0 = b0 + *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_Dmine) + o0);
+            v1 = b1 + *reinterpret_cast<const float *>(reinterpret_cast<const char *>(s_Dmine) + o1);
         } else {
             const uint32_t cw = as_u32(cpk[r2]);
             float e0, e1;
@@ -278,7 +290,7 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
         const float s0 = seq(0), s1 = V == 2 ? seq(1) : 0.f;
         if constexpr (HYB) {
 #pragma unroll
-            for (int j = tid; j < ROWS; j += VT_NT) s_D[j] = hyb_error(j, s0, s1);
+            for (int j = tid; j < ROWS; j += VT_NT) store_error(j, hyb_error(j, s0, s1));
             __syncthreads();
         }
 #pragma unroll
@@ -296,7 +308,7 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
     for (int t = 1; t < G; t++) {
         if constexpr (HYB) {
 #pragma unroll
-            for (int j = tid; j < ROWS; j += VT_NT) s_D[j] = hyb_error(j, seq(V * t), seq(V * t + 1));
+            for (int j = tid; j < ROWS; j += VT_NT) store_error(j, hyb_error(j, seq(V * t), seq(V * t + 1)));
         }
         if constexpr (Geo::SLOT) {
             // prefix hi = (SJ tid + j) NC + c; its predecessors are registers (p SJ + j) NC + c
