@@ -164,11 +164,12 @@ int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code
 /*
  * CPU quantizer, used to make valid inputs and to validate; never on the timed
  * path.  ALL pointers are HOST memory.  Each 16x16 tile of W (m x n row-major
- * fp32) is quantized as one sequence with the Viterbi algorithm on the bitshift
- * trellis (Section 2.3) made tail-biting by Algorithm 4, under squared error.
- * codes_out receives (m/16)*(n/16)*8k words in the format above.  mse_out (may
- * be NULL) receives the mean squared error of the reconstruction.  lut_f16 is a
- * host copy of the HYB table (NULL otherwise).  Uses all host cores.
+ * fp32; each 32 x 8 block with QTIP_CODE_LUT) is quantized as one sequence with the
+ * Viterbi algorithm on the bitshift trellis (Section 2.3) made tail-biting by
+ * Algorithm 4, under squared error.  codes_out receives m*n/256 * 8k words in the
+ * format above.  mse_out (may be NULL) receives the mean squared error of the
+ * reconstruction.  lut_f16 is a host copy of the code's table (NULL for the computed
+ * codes).  Binary64 search.  Uses all host cores.
  */
 int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id,
                   const void *lut_f16, uint32_t *codes_out, double *mse_out);
@@ -178,9 +179,10 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
  * quantized as one sequence by the Viterbi algorithm on the bitshift trellis
  * (Section 2.3), made tail-biting by Algorithm 4, under squared error against the
  * code's values (Algorithms 1-3) -- run on the device, one workgroup per tile with
- * the 2^16-entry value function held in registers.
+ * the 2^16-entry value function held in registers.  (QTIP_CODE_LUT: every 32 x 8 block,
+ * 2^14 states; read 32 x 8 for 16 x 16 below.)
  *   W:          device, m x n row-major fp32.
- *   lut_f16:    device HYB table (NULL otherwise).
+ *   lut_f16:    device table of the code (NULL for the computed codes).
  *   codes_out:  device, (m/16)*(n/16)*8k words, the format above.
  *   tile_err:   device, (m/16)*(n/16) floats, or NULL: the final value of the
  *               search for each tile = its squared reconstruction error, as
@@ -190,8 +192,9 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
  *               qtip_quantize_gpu_workspace(k, V, 1) up works; tiles are processed
  *               in batches of as many as fit, so give it
  *               qtip_quantize_gpu_workspace(k, V, t) for t of a few thousand (about
- *               1 MiB per tile at V = 1, 0.5 MiB or less at V = 2) to keep the
- *               device full.  Contents are scratch.
+ *               1 MiB per tile at V = 1, 0.5 MiB or less at V = 2; sized for L = 16,
+ *               QTIP_CODE_LUT uses a quarter of it) to keep the device full.
+ *               Contents are scratch.
  * The search runs in binary32 with fixed roundings (e = c - s; V = 1: value =
  * fma(e, e, minimum over predecessors); V = 2: value = minimum + fma(e1, e1, e0*e0)),
  * lowest predecessor and lowest final state on ties; the paper does not fix a
