@@ -340,10 +340,17 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
                     if ((f & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            // A thread's F minima are one row of F floats.  Written as they stand, the 16-byte
+            // stores of neighbouring lanes would be a whole row apart and land on two of the
+            // eight 16-byte bank groups; with 16 floats per row the four pieces of row T are
+            // therefore kept rotated by (T / 2) % 4 places, which spreads eight lanes over all
+            // eight groups both here and where the rows are read back, four prefixes at a time.
 #pragma unroll
-            for (int f = 0; f < F; f += 4)
-                *reinterpret_cast<float4_t *>(&s_best[tid * F + f]) =
+            for (int f = 0; f < F; f += 4) {
+                const int piece = F == 16 ? ((f >> 2) + (tid >> 1)) & 3 : f >> 2;
+                *reinterpret_cast<float4_t *>(&s_best[tid * F + 4 * piece]) =
                     float4_t{bests[f], bests[f + 1], bests[f + 2], bests[f + 3]};
+            }
             my_ptrs[(size_t)t * PW + tid] = word;
         } else if constexpr (Geo::LOCAL) {
             // prefix hi = NT h + tid; its predecessors p 2^OV + hi are registers p NB1 + h
@@ -400,7 +407,12 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
             for (int p = 0; p < NC; p++) {
                 float b[Geo::SJ];
                 if constexpr (Geo::SJ == 4) {
-                    const float4_t t4 = *reinterpret_cast<const float4_t *>(&s_best[p * (NP / NC) + tid * 4]);
+                    // prefixes p NP/NC + 4 tid .. + 3 are piece tid % 4 of row T = p NT/4 + tid / 4,
+                    // kept at place (tid % 4 + T / 2) % 4 of that row (p NT/8 is a multiple of 4)
+                    static_assert(Geo::SJ * NC == 16 && (VT_NT / 8) % 4 == 0, "row rotation");
+                    const int place = ((tid & 3) + (tid >> 3)) & 3;
+                    const float4_t t4 =
+                        *reinterpret_cast<const float4_t *>(&s_best[p * (NP / NC) + (tid & ~3) * 4 + place * 4]);
                     b[0] = t4[0], b[1] = t4[1], b[2] = t4[2], b[3] = t4[3];
                 } else {
 #pragma unroll
