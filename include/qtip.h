@@ -192,7 +192,8 @@ int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id
  *               qtip_quantize_gpu_workspace(k, V, 1) up works; tiles are processed
  *               in batches of as many as fit, so give it
  *               qtip_quantize_gpu_workspace(k, V, t) for t of a few thousand (about
- *               1 MiB per tile at V = 1, 0.5 MiB or less at V = 2; sized for L = 16,
+ *               2 MiB per tile at k = 2, V = 1, 1 MiB at k = 3 or 4, 0.5 MiB or less at
+ *               V = 2; sized for L = 16,
  *               QTIP_CODE_LUT uses a quarter of it) to keep the device full.
  *               Contents are scratch.
  * The search runs in binary32 with fixed roundings (e = c - s; V = 1: value =

@@ -66,7 +66,14 @@ struct VitGeo {
     // LDS operations).  SJ = mids per thread: mid = SJ tid + j.
     static constexpr bool SLOT = KV <= 3;
     static constexpr int SJ = SLOT ? VT_REGS / (NC * NC) : 1;
-    static constexpr int PW = SLOT ? NT : LOCAL ? NT * PWT : NP;  // back-pointer words per step
+    // kV = 2, 1024 threads: the back-pointer of a prefix is kept as the three outcomes of the
+    // comparisons that found its minimum (v1 < v0, v3 < v2, min23 < min01) instead of the
+    // index they imply: a comparison's lane mask goes straight into the packed word as the
+    // carry of an add (word = 2 word + carry), and no instruction ever forms the index.  16
+    // prefixes x 3 bits are two words per thread and step: prefix f is bits 3 (f % 8) ..
+    // + 2 of word f / 8, comparison outcomes in the order above from bit 2 down.
+    static constexpr bool RAW3 = KV == 2 && NT == 1024;
+    static constexpr int PW = RAW3 ? 2 * NT : SLOT ? NT : LOCAL ? NT * PWT : NP;  // back-pointer words per step
 };
 
 __host__ __device__ constexpr int vit_max(int a, int b) { return a > b ? a : b; }
@@ -131,6 +138,14 @@ __device__ __forceinline__ float argmin_tournament(const float (&val)[VT_REGS], 
         asm("v_min_f32 %0, %1, %2" : "=v"(m) : "v"(a), "v"(b));
         return m;
     }
+}
+// lt = b < a; word = 2 word + lt; m = min(a, b): the comparison's mask is consumed as the carry
+// of the add that follows it (ties: lt = 0, the left operand, as everywhere).
+__device__ __forceinline__ void compare_shift_min(float a, float b, uint32_t &word, float &m) {
+    asm("v_cmp_lt_f32 vcc, %3, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc\n\tv_min_f32 %1, %2, %3"
+        : "+v"(word), "=v"(m)
+        : "v"(a), "v"(b)
+        : "vcc");
 }
 // word = 2 word + (this lane's bit of mask): one add-with-carry.
 __device__ __forceinline__ void shift_in_bit(uint32_t &word, uint64_t mask) {
@@ -320,7 +335,19 @@ __global__ __launch_bounds__((VitGeo<KV, code_state_bits(CODE)>::NT), 4) void vi
             // scalar instructions then overlap other waves' vector work.  With one 16-wave
             // workgroup per CU all waves reach this point together, the scalar unit (one per
             // CU) becomes the queue, and the select chains are faster (4.69 against 4.91 us).
-            if constexpr (VT_NT <= 256) {
+            if constexpr (Geo::RAW3) {
+                uint32_t words[2] = {0u, 0u};
+#pragma unroll
+                for (int f = F - 1; f >= 0; f--) {
+                    float m01, m23;
+                    compare_shift_min(val[f], val[f + F], words[f >> 3], m01);
+                    compare_shift_min(val[f + 2 * F], val[f + 3 * F], words[f >> 3], m23);
+                    compare_shift_min(m01, m23, words[f >> 3], bests[f]);
+                    if ((f & 3) == 0) __builtin_amdgcn_sched_barrier(0);
+                }
+                my_ptrs[(size_t)t * PW + VT_NT + tid] = words[1];
+                word = words[0];
+            } else if constexpr (VT_NT <= 256) {
                 // prefixes from the last to the first and bits from the top down, so that prefix
                 // f ends up in bits f kV .. f kV + kV - 1 of the word
 #pragma unroll
@@ -508,7 +535,12 @@ __global__ __launch_bounds__(64) void viterbi_backtrace_kernel(
         if (t == stop) break;
         const uint32_t hi = arg >> KV;
         uint32_t p;
-        if constexpr (Geo::SLOT) {
+        if constexpr (Geo::RAW3) {
+            const uint32_t f = hi % 16;  // prefix hi is prefix f of thread hi / 16
+            const uint32_t word = my_ptrs[(size_t)t * PW + (f >> 3) * VT_NT + hi / 16];
+            const uint32_t bits = (word >> (3 * (f & 7))) & 7u;  // (v1 < v0, v3 < v2, min23 < min01)
+            p = (bits & 1u) ? 2u + ((bits >> 1) & 1u) : (bits >> 2);
+        } else if constexpr (Geo::SLOT) {
             constexpr uint32_t F = Geo::SJ * NC;  // prefix hi is field hi % F of thread hi / F
             const uint32_t word = my_ptrs[(size_t)t * PW + hi / F];
             p = (word >> ((hi % F) * KV)) & (uint32_t)(NC - 1);
