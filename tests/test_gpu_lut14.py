@@ -247,6 +247,24 @@ def test_quantizer_streams_equal_the_binary32_oracle(q, k):
             assert err[I * (n // 8) + J] == d
 
 
+def test_quantizer_degenerate_blocks_equal_the_binary32_oracle(q):
+    """Blocks of zeros, of one constant, of weights 30 times the table's spread and with one
+    outlier of 1e4: streams and final values bit for bit."""
+    k = 2
+    rng = np.random.default_rng(1450)
+    lut = rng.standard_normal(1 << 14).astype(np.float16)
+    C = oracle.codebook(14, 1, CODE_LUT, lut)
+    outlier = rng.standard_normal((32, 8))
+    outlier[rng.integers(32), rng.integers(8)] = 1e4
+    blocks = [np.zeros((32, 8)), np.full((32, 8), 0.37), rng.standard_normal((32, 8)) * 30, outlier]
+    W = np.concatenate(blocks, axis=1).astype(np.float32)
+    codes, err = run_quantize_gpu(q, W, k, lut)
+    for J in range(len(blocks)):
+        d, words = oracle.tailbiting_quantize_f32(W[:, 8 * J:8 * J + 8].reshape(-1), 14, k, 1, C)
+        assert np.array_equal(codes[J], words), J
+        assert err[J] == d
+
+
 def test_quantizer_roundtrip_and_distortion(q):
     """Weights that are decodable come back exactly; on Gaussian input every block's reported
     error is the binary64 distortion of its own stream, and the mean squared error agrees with

@@ -72,6 +72,28 @@ def test_streams_and_values_equal_the_binary32_oracle(q, code_id, k, V):
         assert err[J] == d
 
 
+@pytest.mark.parametrize("code_id,k,V", [(CODE_3INST, 2, 1), (CODE_1MAD, 4, 1), (CODE_HYB, 3, 2), (CODE_HYB1, 2, 1)])
+def test_degenerate_tiles_equal_the_binary32_oracle(q, code_id, k, V):
+    """Tiles far from the Gaussian case: all zeros and a constant (many paths of nearly
+    equal cost), weights 30 times the code's spread (every state far away), heavy tails,
+    and one outlier of 1e4 among ordinary weights (costs near 1e8 beside costs near 1).
+    Streams and final values bit for bit, as for ordinary tiles."""
+    rng = np.random.default_rng(5000 + 10 * code_id + k)
+    lut = make_lut(code_id, rng)
+    C = oracle.codebook(16, V, code_id, lut)
+    sd = C.std()
+    outlier = rng.standard_normal((16, 16)) * sd
+    outlier[rng.integers(16), rng.integers(16)] = 1e4
+    tiles = [np.zeros((16, 16)), np.full((16, 16), 0.37 * sd), rng.standard_normal((16, 16)) * sd * 30,
+             rng.standard_t(2, (16, 16)) * sd, outlier]
+    W = np.concatenate(tiles, axis=1).astype(np.float32)
+    codes, err = run_quantize_gpu(q, W, k, V, code_id, lut)
+    for J in range(len(tiles)):
+        d, words = oracle.tailbiting_quantize_f32(tile_sequence(W, 0, J), 16, k, V, C)
+        assert np.array_equal(codes[J], words), (J, codes[J], words)
+        assert err[J] == d
+
+
 def test_decodable_weights_come_back_exactly(q):
     rng = np.random.default_rng(8)
     for code_id, k, V in [(CODE_3INST, 2, 1), (CODE_1MAD, 3, 1), (CODE_HYB, 2, 2), (CODE_HYB2, 4, 2)]:
