@@ -41,6 +41,10 @@
  *   QTIP_CODE_HYB1 (Q = 6) with L = 16, V = 1 and k in {2, 3, 4}; m and n
  *   multiples of 16.  QTIP_CODE_LUT with L = 14, V = 1 and k in {2, 3, 4}; m a multiple of
  *   32, n of 8.  Anything else returns QTIP_EUNSUPPORTED / QTIP_EINVAL.
+ *   Sizes: m, n and batch sizes are ints; every offset into codes, weights, activations
+ *   and outputs is formed in 64 bits, so buffers may pass 4 GiB (checked on 98304 x 98304
+ *   at 4 bits).  The calls that record nothing but kernel launches (all of the GPU entry
+ *   points) may be captured into a HIP graph.
  *
  * OWNERSHIP, STREAMS, ERRORS
  *   The caller owns every buffer.  GPU entry points take device pointers, enqueue

@@ -252,6 +252,51 @@ def test_full_size_configs(q, name):
         assert np.array_equal(got_mv, got)          # same kernel, deterministic
 
 
+@pytest.mark.parametrize("code_id,k,V", [(CODE_3INST, 4, 1), (CODE_HYB, 4, 2)])
+def test_offsets_beyond_32_bits(q, code_id, k, V):
+    """98304 x 98304 at 4 bits: 4.8 GB of codes (byte offsets pass 2^32, word offsets 2^30),
+    9.7e9 weights (element offsets pass 2^33).  The stream is drawn on the device; the oracle
+    gets the tile rows of the sampled outputs, the last tile row among them, and decodes those
+    rows one element at a time."""
+    import torch
+    m = n = 98304
+    tn, nw = n // 16, 8 * k
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234 + code_id)
+    codes = torch.randint(-2 ** 31, 2 ** 31 - 1, ((m // 16) * tn, nw), dtype=torch.int32, device="cuda",
+                          generator=gen)
+    rng = np.random.default_rng(77 + code_id)
+    lut_h = rng.standard_normal((512, 2)).astype(np.float16) if code_id == CODE_HYB else None
+    lut = dev(lut_h)
+    X_h = rng.standard_normal((3, n)).astype(np.float16)
+    X = dev(X_h)
+    rows = np.array([5, 43690, 43691, 65535, 65536, 87381, m - 1])   # around 2^31 and 2^32 elements, and the end
+    W = torch.empty((m, n), dtype=torch.float16, device="cuda")
+    q.qtip_dequantize(codes, 16, k, V, code_id, lut, m, n, W)
+    y = torch.full((m,), float("nan"), dtype=torch.float32, device="cuda")
+    q.qtip_decode_matvec(codes, 16, k, V, code_id, lut, m, n, X[0], y)
+    Y = torch.full((3, m), float("nan"), dtype=torch.float32, device="cuda")
+    q.qtip_decode_matmat(codes, 16, k, V, code_id, lut, m, n, X, 3, None, Y)
+    torch.cuda.synchronize()
+    y_h, Y_h = y.cpu().numpy(), Y.cpu().numpy()
+    assert np.all(np.isfinite(y_h)) and np.all(np.isfinite(Y_h))
+    refs = []
+    for i in rows:
+        I, r = int(i) // 16, int(i) % 16
+        band = codes[I * tn:(I + 1) * tn].cpu().numpy().view(np.uint32)        # this tile row's streams
+        cols = list(range(0, n, 997)) + [n - 2, n - 1]
+        want = np.array([oracle.decode_element(band, 16, k, V, code_id, n, r, j, lut_h) for j in cols],
+                        dtype=np.uint16)
+        got = W[int(i)].cpu().numpy().view(np.uint16)[cols]
+        assert np.array_equal(got, want), i
+        refs.append(oracle.decode_matmat_rows(band, 16, k, V, code_id, 16, n, X_h, [r], lut_h)[:, 0])
+    ref = np.stack(refs, axis=1)                                                 # (3, len(rows))
+    err = float(np.abs(Y_h[:, rows] - ref).max() / np.abs(ref).max())
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    err = float(np.abs(y_h[rows] - ref[0]).max() / np.abs(ref[0]).max())
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+
+
 # ------------------------------------------------------------------ Hadamard
 
 @pytest.mark.parametrize("block", [16, 32, 64, 256, 1024, 2048, 4096, 8192, 16384])
