@@ -109,3 +109,40 @@ def test_quantizer_replayed_from_a_graph(q):
         torch.cuda.synchronize()
         assert torch.equal(codes, want[0]), replay
         assert torch.equal(err.view(torch.int32), want[1].view(torch.int32)), replay
+
+
+def test_calls_on_two_streams_at_once(q):
+    """No state is shared between calls: two layers enqueued on two streams with an explicit
+    stream argument, overlapping in time, give the bits of the same calls made one after the
+    other on the default stream."""
+    import torch
+    m, n, k = 2048, 8192, 2
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    jobs = []
+    for j, code_id in enumerate((CODE_3INST, CODE_HYB)):
+        V = 2 if code_id == CODE_HYB else 1
+        w = synth.Workload("two_streams", 9, 20 + j, m, n, code_id, k, V, 4096, 2048)
+        inp = synth.make_inputs(w)
+        jobs.append(dict(code_id=code_id, V=V, codes=dev(inp.codes), lut=dev(inp.lut), x=dev(inp.X), sn=dev(inp.signs_n),
+                         xt=torch.empty((1, n), dtype=torch.float16, device="cuda"),
+                         y=torch.empty(m, dtype=torch.float32, device="cuda")))
+
+    def run(job, stream):
+        q.qtip_rht(job["x"], job["sn"], n, 4096, 1, 0, job["xt"], stream=stream)
+        q.qtip_decode_matvec(job["codes"], 16, k, job["V"], job["code_id"], job["lut"], m, n, job["xt"], job["y"],
+                             stream=stream)
+
+    for job in jobs:
+        run(job, None)
+    torch.cuda.synchronize()
+    want = [job["y"].clone() for job in jobs]
+    for rep in range(5):
+        for job in jobs:
+            job["y"].fill_(float("nan"))
+            job["xt"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        for job, st in zip(jobs, streams):
+            run(job, st)
+        torch.cuda.synchronize()
+        for job, ref in zip(jobs, want):
+            assert torch.equal(job["y"].view(torch.int32), ref.view(torch.int32)), rep
