@@ -130,3 +130,45 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2406_11235_amd" not in text and "libqtip.so" not in text, f
+
+
+C_PROGRAM = r"""
+#include "qtip.h"
+#include <stdio.h>
+#include <string.h>
+int main(void) {
+    unsigned int word[16] = {0};
+    float y[16];
+    if (qtip_version() != QTIP_VERSION) return 1;
+    /* n = 24 is not a multiple of 16: refused before any GPU work */
+    if (qtip_decode_matvec(word, 16, 2, 1, QTIP_CODE_3INST, NULL, 16, 24, word, y, NULL) != QTIP_EINVAL) return 2;
+    if (strlen(qtip_last_error()) == 0) return 3;
+    if (qtip_quantize_gpu_workspace(2, 1, 1) == 0) return 4;
+    puts("ok");
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(q, tmp_path):
+    """The boundary is usable without Python or C++: the header compiles as strict C99 (and as
+    C++), and a C program linked against libqtip.so runs its argument checks on a machine
+    without a GPU."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.dirname(q.library_path())
+    src = tmp_path / "abi.c"
+    src.write_text(C_PROGRAM)
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)],
+                   check=True)
+    subprocess.run([shutil.which("g++") or "g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                    "-x", "c++", "-I", inc, str(src)], check=True)
+    exe = tmp_path / "abi"
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lqtip",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    assert out.stdout.strip() == "ok"
