@@ -27,13 +27,45 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 WORKLOAD = "metric_3inst_k2_8192x28672"
 
-# HBM bytes per launch of the decode + matvec kernel on this workload, from
-# `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this file (summaries in
-# profiles/), scaled by what the same counters read for a plain copy of known size.
-# profiles/matvec_3inst_k2_8192x28672_traffic.txt: FETCH_SIZE 28956.4 KiB x 1.9998 (the copy kernel reads
-# half of what it moves on this counter) + WRITE_SIZE 32.0 KiB x 1.0000.
-MEASURED_TRAFFIC_BYTES = {"metric_3inst_k2_8192x28672": 59329719}
-MEASURED_VALU_WAVE_INSTS = {"metric_3inst_k2_8192x28672": 19548160}
+# Counter figures for the decode + matvec kernel come from rocprofv3 --pmc runs of this file,
+# whose summaries live in profiles/<workload>_counters.txt as `key = value` lines: HBM bytes per
+# launch (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain copy
+# of known size), vector-ALU wave instructions per launch (SQ_INSTS_VALU), and the SHA-256 of the
+# kernel sources they were measured on.  They are reported only while that hash still matches
+# the sources in the tree; after any kernel change they are dropped until the profile is redone.
+PROFILE_DIR = os.path.join(ROOT, "profiles")
+KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2406_11235_amd", "csrc")
+
+
+def kernel_sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(KERNEL_SOURCE_DIR)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            with open(os.path.join(KERNEL_SOURCE_DIR, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_counters(workload):
+    """{key: value} from profiles/<workload>_counters.txt, or {} if the file is missing or was
+    taken on other kernel sources than the tree holds (said on stderr)."""
+    path = os.path.join(PROFILE_DIR, workload + "_counters.txt")
+    if not os.path.exists(path):
+        return {}
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            if "=" in line and not line.lstrip().startswith("#"):
+                key, v = line.split("=", 1)
+                vals[key.strip()] = v.strip()
+    if vals.get("kernel_sources_sha256") != kernel_sources_sha256():
+        log(f"bench.py: {os.path.relpath(path, ROOT)} was measured on other kernel sources than the "
+            f"tree holds: its counter figures (traffic, vector-ALU instructions) are left out")
+        return {}
+    vals["file"] = os.path.relpath(path, ROOT)
+    return vals
 
 
 def log(*a):
@@ -111,10 +143,10 @@ def bench_quantize(args, q, torch, np):
     A = torch.empty((n, n), dtype=torch.float32, device="cuda")
     lws_bytes = q.qtip_block_ldl_workspace(n)
     lws = torch.empty(lws_bytes, dtype=torch.uint8, device="cuda")
-    q.qtip_block_ldl(H, n, A, None, lws, lws_bytes)
+    q.qtip_block_ldl(H, n, 16, A, None, lws, lws_bytes)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    q.qtip_block_ldl(H, n, A, None, lws, lws_bytes)
+    q.qtip_block_ldl(H, n, 16, A, None, lws, lws_bytes)
     torch.cuda.synchronize()
     ms_ldl = (time.perf_counter() - t0) * 1e3
     del lws
@@ -214,20 +246,44 @@ def main():
             q.qtip_decode_matmat(codes, w.L, w.k, w.V, w.code_id, st["lut"], w.m, w.n, st["xt"],
                                  w.B, st["scale"], st["Y"])
 
-    def timed(fn, steps, warmup):
-        """Average ms per call of fn(i), HIP events on the launch stream."""
-        for i in range(warmup):
-            fn(i)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ROUNDS = 11          # timed rounds of `steps` launches each; the median round is reported
+    MIN_WARM_MS = 50.0   # warm-up lasts at least this long (clocks ramp over some milliseconds)
+
+    class Timing(float):
+        """Median ms per call over the rounds (the float), plus the spread."""
+        def __new__(cls, per_round):
+            per_round = sorted(per_round)
+            self = super().__new__(cls, per_round[len(per_round) // 2])
+            self.min, self.max, self.rounds = per_round[0], per_round[-1], len(per_round)
+            return self
+
+    def warm(fn, warmup):
+        """`warmup` calls, then more of the same until MIN_WARM_MS of wall time have passed."""
         t0 = time.perf_counter()
-        e0.record()
-        for i in range(steps):
-            fn(i)
-        e1.record()
-        torch.cuda.synchronize()
-        wall = (time.perf_counter() - t0) * 1e3 / steps
-        return e0.elapsed_time(e1) / steps, wall
+        i = 0
+        while True:
+            for _ in range(max(1, warmup)):
+                fn(i)
+                i += 1
+            torch.cuda.synchronize()
+            if (time.perf_counter() - t0) * 1e3 >= MIN_WARM_MS:
+                return i
+
+    def timed(fn, steps, warmup):
+        """ms per call of fn(i): ROUNDS rounds of exactly `steps` calls, each bracketed by HIP
+        events on the launch stream; the median round is the figure, min and max go with it."""
+        i = warm(fn, warmup)
+        events = []
+        for _ in range(ROUNDS):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn(i)
+                i += 1
+            e1.record()
+            torch.cuda.synchronize()
+            events.append((e0, e1))
+        return Timing([a.elapsed_time(b) / steps for a, b in events])
 
     def timed_graph(step, period, steps, warmup):
         """The same steps captured once into a HIP graph (`period` steps = one pass over
@@ -243,19 +299,18 @@ def main():
         with torch.cuda.graph(g):
             for i in range(period):
                 step(i)
-        replays, rest = divmod(steps, period)
-        for _ in range(max(1, warmup // period)):
-            g.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(replays):
-            g.replay()
-        for i in range(rest):
-            step(i)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps
+        replays = max(1, -(-steps // period))
+        warm(lambda i: g.replay(), max(1, warmup // period))
+        events = []
+        for _ in range(ROUNDS):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(replays):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            events.append((e0, e1))
+        return Timing([a.elapsed_time(b) / (replays * period) for a, b in events])
 
     def measure(name, steps, warmup):
         st = prepare(synth.WORKLOADS[name])
@@ -265,46 +320,50 @@ def main():
             rht(st)
             mult(st, i)
 
-        ms_step, wall_step = timed(step, steps, warmup)
+        ms_step = timed(step, steps, warmup)
         ms_step_graph = timed_graph(step, len(st["bufs"]), steps, warmup)
         rht(st)
-        ms_kernel, _ = timed(lambda i: mult(st, i), steps, warmup)
-        ms_hot, _ = timed(lambda i: mult(st, 0), steps, warmup)
-        ms_rht, _ = timed(lambda i: rht(st), steps, warmup)
-        return st, dict(ms_step=ms_step, ms_step_graph=ms_step_graph, wall_step=wall_step,
+        ms_kernel = timed(lambda i: mult(st, i), steps, warmup)
+        ms_hot = timed(lambda i: mult(st, 0), steps, warmup)
+        ms_rht = timed(lambda i: rht(st), steps, warmup)
+        return st, dict(ms_step=ms_step, ms_step_graph=ms_step_graph,
                         ms_kernel=ms_kernel, ms_hot=ms_hot, ms_rht=ms_rht, bytes=w.code_bytes,
                         copies=len(st["bufs"]))
 
     st, r = measure(args.workload, args.steps, args.warmup)
     w = st["w"]
     gbs = lambda ms: w.code_bytes / (ms * 1e-3) / 1e9
-    log(f"[{w.name}] step {r['ms_step']*1e3:.2f} us ({r['ms_step_graph']*1e3:.2f} us replayed from a "
-        f"HIP graph), "
-        f"decode+matvec kernel {r['ms_kernel']*1e3:.2f} us cold = {gbs(r['ms_kernel']):.0f} GB/s "
-        f"({gbs(r['ms_kernel'])/HBM_PEAK_GBS*100:.1f}% of 8 TB/s), {r['ms_hot']*1e3:.2f} us "
+    spread = lambda t: f"{t*1e3:.2f} us (min {t.min*1e3:.2f}, max {t.max*1e3:.2f})"
+    log(f"[{w.name}] median of {ROUNDS} rounds of {args.steps} steps: step {spread(r['ms_step'])}, "
+        f"{r['ms_step_graph']*1e3:.2f} us replayed from a HIP graph; "
+        f"decode+matvec kernel {spread(r['ms_kernel'])} cold = {gbs(r['ms_kernel']):.0f} GB/s "
+        f"({gbs(r['ms_kernel'])/HBM_PEAK_GBS*100:.1f}% of 8 TB/s), {spread(r['ms_hot'])} "
         f"cache-resident, rht {r['ms_rht']*1e3:.2f} us back to back, {r['copies']} rotating buffers")
 
+    counters = measured_counters(w.name)
     # algorithmic bytes per launch: code stream + activation + output
     alg_bytes = w.code_bytes + 2 * w.n * w.B + 4 * w.m * w.B
     roofline = {"bound": "hbm", "kernel": "decode+matvec", "achieved": alg_bytes / (r["ms_kernel"] * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": alg_bytes / (r["ms_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "us_per_launch": r["ms_kernel"] * 1e3,
+                "traffic": int(counters["traffic_bytes_per_launch"]) if "traffic_bytes_per_launch" in counters else None,
+                "traffic_from": counters.get("file"), "us_per_launch": r["ms_kernel"] * 1e3,
+                "us_per_launch_min": r["ms_kernel"].min * 1e3, "us_per_launch_max": r["ms_kernel"].max * 1e3,
                 "us_per_launch_cache_resident": r["ms_hot"] * 1e3,
                 "algorithmic_bytes": alg_bytes}
 
-    # The same kernel against the vector-ALU roof: wave instructions per launch from
-    # profiles/matvec_3inst_k2_8192x28672_valu.txt (SQ_INSTS_VALU), 64 lanes each, against
-    # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second.  Some of the
-    # instructions issue in two cycles instead of four, so the fraction can pass 1.
+    # The same kernel against the vector-ALU roof: wave instructions per launch (SQ_INSTS_VALU),
+    # 64 lanes each, against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second
+    # (the rate of the four-cycle instructions that make up most of the loop; the simplest
+    # 32-bit operations issue in two cycles, so the fraction could pass 1 for other code).
     valu = None
-    if w.name in MEASURED_VALU_WAVE_INSTS:
-        lane_ops = MEASURED_VALU_WAVE_INSTS[w.name] * 64
+    if "valu_wave_instructions_per_launch" in counters:
+        winsts = int(counters["valu_wave_instructions_per_launch"])
         peak = 256 * 4 * 16 * 2.4e9
         valu = {"bound": "alu", "kernel": "decode+matvec", "unit": "T lane-instructions/s",
-                "achieved": lane_ops / (r["ms_hot"] * 1e-3) / 1e12, "peak": peak / 1e12,
-                "frac": lane_ops / (r["ms_hot"] * 1e-3) / peak,
-                "valu_wave_instructions_per_launch": MEASURED_VALU_WAVE_INSTS[w.name]}
+                "achieved": winsts * 64 / (r["ms_hot"] * 1e-3) / 1e12, "peak": peak / 1e12,
+                "frac": winsts * 64 / (r["ms_hot"] * 1e-3) / peak,
+                "valu_wave_instructions_per_launch": winsts, "counters_from": counters["file"]}
 
     # The lookup-only code is bound by its table reads: one 2-byte LDS read per weight at random
     # addresses.  Peak: 32 four-byte banks per CU, each serving one address per cycle.
@@ -373,14 +432,15 @@ def main():
         "metric": "batch-1 decode+matvec effective HBM GB/s on compressed-weight bytes, "
                   + ("2-bit 3INST 8192x28672" if w.name == WORKLOAD else w.name),
         "value": gbs(r["ms_step"]), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": r["ms_step"], "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": float(r["ms_step"]), "ms_per_step_min": r["ms_step"].min,
+        "ms_per_step_max": r["ms_step"].max, "rounds": ROUNDS, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "m": w.m, "n": w.n, "code": synth.CODE_NAMES[w.code_id],
                    "L": w.L, "k": w.k, "V": w.V, "batch": w.B, "rht_block": w.block_n,
                    "step": "qtip_rht + qtip_decode_matvec",
                    "rotating_code_buffers": r["copies"]},
         "us_per_matvec": r["ms_kernel"] * 1e3, "us_rht": r["ms_rht"] * 1e3,
-        "ms_per_step_hipgraph": r["ms_step_graph"],
+        "ms_per_step_hipgraph": float(r["ms_step_graph"]),
         "pct_of_hbm_peak": gbs(r["ms_kernel"]) / HBM_PEAK_GBS * 100,
         "roofline": roofline, "roofline_alu": valu, "roofline_lds": lds, "cpu_baseline": cpu_baseline,
     }

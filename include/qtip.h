@@ -121,10 +121,11 @@ int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
  * Batched form: Y[b][i] = row_scale[i] * sum_j W~[i][j] * X[b][j], b < B.
  * X_f16: device, B x n row-major fp16.  Y: device, B x m row-major fp32,
  * overwritten.  row_scale_f16: device, m fp16, or NULL for no scale.  B >= 1.
- * Small B runs on the vector ALUs, larger B on the matrix cores (MFMA) with the
- * decoded 16x16 tile as one operand (Section 4: T_x = T_y = 16 matches a 16x16
- * matrix-multiply tile).  With QTIP_CODE_LUT every B >= 2 runs on the matrix cores: two
- * neighbouring 32 x 8 blocks are the 32 x 16 operand of the 32x32x16 instruction.
+ * B = 1 runs the batch-1 kernel on the vector ALUs; every B >= 2 runs on the matrix cores
+ * (MFMA) with the decoded 16x16 tile as one operand (Section 4: T_x = T_y = 16 matches a
+ * 16x16 matrix-multiply tile; with QTIP_CODE_LUT two neighbouring 32 x 8 blocks are the
+ * 32 x 16 operand of the 32x32x16 instruction).  Y must be 16-byte aligned (and m a multiple
+ * of 16, as everywhere): outputs are stored four at a time.
  */
 int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id,
                        const void *lut_f16, int m, int n, const void *X_f16, int B,
@@ -173,7 +174,9 @@ int qtip_decode_states(const uint32_t *states, int count, int L, int V, int code
  * Algorithm 4, under squared error.  codes_out receives m*n/256 * 8k words in the
  * format above.  mse_out (may be NULL) receives the mean squared error of the
  * reconstruction.  lut_f16 is a host copy of the code's table (NULL for the computed
- * codes).  Binary64 search.  Uses all host cores.
+ * codes).  Binary64 search.  Starts one worker thread per tile up to
+ * std::thread::hardware_concurrency() (all host cores; there is no way to ask for fewer) and
+ * joins them before it returns.
  */
 int qtip_quantize(const float *W, int m, int n, int L, int k, int V, int code_id,
                   const void *lut_f16, uint32_t *codes_out, double *mse_out);
@@ -246,7 +249,8 @@ int qtip_block_ldl(const double *H, int n, int g, float *A_out, double *D_out, v
  *   that helps; any t >= 1 works; the size is computed for 16 x 16 blocks and covers 32 x 8).
  * The feedback sum is binary32, one fused multiply-add per term, column blocks from the last
  * one down and ascending inside a block, so that the input of the quantizer is reproducible.
- * The workspace holds a running m x n fp32 sum besides the quantizer's own.
+ * The workspace holds a running m x n fp32 sum besides the quantizer's own: on return its
+ * first m*n floats are x of Algorithm 5, row-major, every column block as it was rounded.
  */
 size_t qtip_quantize_ldlq_workspace(int m, int n, int k, int V, long tiles);
 int qtip_quantize_ldlq(const float *W, const float *A, int m, int n, int L, int k, int V, int code_id,

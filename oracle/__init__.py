@@ -27,7 +27,11 @@ def _q(code_id, Q):
 
 
 def build(force=False):
-    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    """Compile the oracle with gcc (no fast-math, no FMA contraction).
+    QTIP_ORACLE_LIBRARY names another build of the same source to load instead (the sanitizer
+    leg of the tests builds one with -fsanitize=address,undefined)."""
+    if os.environ.get("QTIP_ORACLE_LIBRARY"):
+        return os.environ["QTIP_ORACLE_LIBRARY"]
     if (not force and os.path.exists(_LIB)
             and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
         return _LIB

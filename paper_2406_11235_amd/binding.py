@@ -12,7 +12,8 @@ import numpy as np
 CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT, CODE_HYB1 = 0, 1, 2, 3, 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# QTIP_LIBRARY points at another build of the same library (e.g. to compare two builds)
+# The environment variable QTIP_LIBRARY names another build of the same library to load instead
+# (two builds compared on one box; the sanitizer build of the host code in tests/test_sanitizers.py).
 _LIB_PATH = os.environ.get("QTIP_LIBRARY") or os.path.join(_HERE, "libqtip.so")
 _lib = None
 
@@ -186,7 +187,7 @@ def qtip_block_ldl_workspace(n):
     return int(lib().qtip_block_ldl_workspace(n))
 
 
-def qtip_block_ldl(H, n, A_out, D_out, workspace, workspace_bytes, stream=None, g=16):
+def qtip_block_ldl(H, n, g, A_out, D_out, workspace, workspace_bytes, stream=None):
     return _check(lib().qtip_block_ldl(_ptr(H), n, g, _ptr(A_out), _ptr(D_out), _ptr(workspace),
                                        workspace_bytes, _stream(stream)))
 

@@ -146,7 +146,8 @@ int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id, 
     if (int rc = check_codec(fn, codes, L, k, V, code_id, lut_f16, m, n)) return rc;
     if (!X_f16 || !Y) return fail(QTIP_EINVAL, "%s: NULL pointer", fn);
     if (B < 1 || B > 65535 * 64) return fail(QTIP_EINVAL, "%s: B = %d out of range", fn, B);
-    if (!aligned(X_f16, 16)) return fail(QTIP_EINVAL, "%s: X must be 16-byte aligned", fn);
+    if (!aligned(X_f16, 16) || !aligned(Y, 16))
+        return fail(QTIP_EINVAL, "%s: X and Y must be 16-byte aligned", fn);
     hipError_t e;
     if (B == 1)
         e = qtip::launch_matvec(k, code_id, codes, (const uint32_t *)lut_f16, m, n, X_f16,

@@ -10,8 +10,6 @@
 #include "qtip_internal.h"
 #include "qtip_rht_device.h"
 
-#include <cstdlib>
-
 namespace qtip {
 
 // The same plus the first word of the next lane of the same tile (cyclically: the
@@ -458,11 +456,6 @@ static hipError_t launch_dequantize_t(const uint32_t *codes, const uint32_t *lut
 // many steps each wave runs: few steps leave a wave's start-up and reduction exposed,
 // few waves leave SIMDs idle or the vector ALU short of waves to interleave.
 static int pick_matvec_waves(int tm, int steps_per_row) {
-    static const char *env = getenv("QTIP_MATVEC_WAVES");  // tuning override: 2, 4, 8 or 16
-    if (env) {
-        const int v = atoi(env);
-        if (v == 2 || v == 4 || v == 8 || v == 16) return v;
-    }
     (void)tm;
     // measured on the configured shapes: occupancy matters more than steps per wave;
     // 16 waves win once a wave still gets 4 steps, 8 are best for mid-sized rows
@@ -476,8 +469,6 @@ static int pick_matvec_waves(int tm, int steps_per_row) {
 // (measured: 8192 x 28672 29.9 -> 22.5 us at k = 2, 8192 x 8192 10.0 -> 9.6, 14336 x 4096 10.0 ->
 // 12.0).  The two-sign-flip form is bound by its vector instructions and gains nothing.
 static bool pick_hyb_spread(int code, int n) {
-    static const char *env = getenv("QTIP_HYB_SPREAD");  // tuning override: 0 or 1
-    if (env) return atoi(env) != 0;
     return code == CODE_HYB && n >= 8192;
 }
 

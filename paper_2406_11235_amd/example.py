@@ -42,7 +42,7 @@ def main(m=1024, n=2048, seed=0):
     What = torch.empty(m, n, device=dev)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    qtip_block_ldl(H, n, A, None, ws, ws.numel())
+    qtip_block_ldl(H, n, 16, A, None, ws, ws.numel())
     qtip_quantize_ldlq(W, A, m, n, 16, k, V, code, None, codes, What, None, ws, ws.numel())
     torch.cuda.synchronize()
     t_quant = time.perf_counter() - t0

@@ -106,7 +106,10 @@ def test_argument_errors_need_no_gpu(q):
         assert rc == want, (i, rc, want, q.qtip_last_error())
     assert "multiple of 16" in q.qtip_last_error()
     assert L.qtip_decode_states(p, 0, 16, 1, 0, None, p, None) == 0     # empty input: no launch
-    # workspace sizes: 2 MiB of back-pointers per tile at k = 2, V = 1, monotone in tiles
+
+
+def test_workspace_sizes(q):
+    # 2 MiB of back-pointers per tile at k = 2, V = 1, monotone in tiles
     w1, w2 = q.qtip_quantize_gpu_workspace(2, 1, 1), q.qtip_quantize_gpu_workspace(2, 1, 2)
     assert 2 << 20 <= w1 <= (2 << 20) + 4096 and w1 < w2 <= 2 * w1
     assert q.qtip_quantize_gpu_workspace(4, 2, 1) < w1

@@ -36,7 +36,7 @@ def run_block_ldl(q, H):
     D = torch.full((n // 16, 16, 16), float("nan"), dtype=torch.float64, device="cuda")
     wsb = q.qtip_block_ldl_workspace(n)
     ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
-    q.qtip_block_ldl(Hd, n, A, D, ws, wsb)
+    q.qtip_block_ldl(Hd, n, 16, A, D, ws, wsb)
     torch.cuda.synchronize()
     return A.cpu().numpy(), D.cpu().numpy()
 
@@ -143,13 +143,13 @@ def test_ldlq_error_codes(q):
         q.qtip_quantize_ldlq(W, A, 16, 32, 16, 2, 1, CODE_3INST, None, codes, None, None, ws, need - 1)
     assert e.value.code == -1 and "workspace" in str(e.value)
     with pytest.raises(q.QtipError) as e:
-        q.qtip_block_ldl(H, 24, A, None, ws, ws.numel())
+        q.qtip_block_ldl(H, 24, 16, A, None, ws, ws.numel())
     assert e.value.code == -1
     with pytest.raises(q.QtipError) as e:
-        q.qtip_block_ldl(H, 32, A, None, ws, 100)
+        q.qtip_block_ldl(H, 32, 16, A, None, ws, 100)
     assert e.value.code == -1
     assert q.qtip_block_ldl_workspace(24) == 0 and q.qtip_quantize_ldlq_workspace(16, 32, 7, 1, 1) == 0
-    q.qtip_block_ldl(H, 32, A, None, ws, ws.numel())
+    q.qtip_block_ldl(H, 32, 16, A, None, ws, ws.numel())
     q.qtip_quantize_ldlq(W, A, 16, 32, 16, 2, 1, CODE_3INST, None, codes, None, None, ws, need)
     torch.cuda.synchronize()
     assert float(A.abs().max()) == 0.0          # H = I: no feedback

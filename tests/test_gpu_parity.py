@@ -214,39 +214,34 @@ FULL = ["cfg1_3inst_k2_1024x1024", "cfg2_3inst_k2_4096x4096", "cfg3_1mad_k2_1433
         "next_hyb1_k2_8192x28672"]
 
 
-def sample_rows(w, rng, count=48):
-    """A whole tile row, the first and last rows, and random rows."""
-    I = int(rng.integers(0, w.m // 16))
-    rows = set(range(16 * I, 16 * I + 16)) | {0, w.m - 1}
-    rows |= set(int(r) for r in rng.integers(0, w.m, count))
-    return np.array(sorted(rows), dtype=np.int32)
+def assert_products_match(got, ref):
+    """The stated bar (max error over max output, 2e-3), what fp32 accumulation actually gives,
+    and the element-wise form of the bar: |y - y*| <= 2e-3 |y*| + 2e-3 rms(y*) for every output."""
+    err = float(np.abs(got - ref).max() / np.abs(ref).max())
+    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    rms = float(np.sqrt((ref ** 2).mean()))
+    excess = np.abs(got - ref) - (REL_TOL * np.abs(ref) + REL_TOL * rms)
+    assert excess.max() <= 0.0, (float(excess.max()), int(excess.argmax()))
 
 
 @pytest.mark.parametrize("name", FULL)
 def test_full_size_configs(q, name):
-    """The configured shapes in the launch configuration the benchmark times."""
+    """The configured shapes in the launch configuration the benchmark times: every decoded
+    weight (bit patterns) and every output against the oracle's whole-matrix decode and its
+    fp64 dense product."""
+    import gc
     w = synth.WORKLOADS[name]
     inp = synth.make_inputs(w)
-    rng = np.random.default_rng(w.seed + 7)
-    rows = sample_rows(w, rng)
-    # decoded weights: sampled rows, bit-exact
+    ref_W = oracle.dequantize(inp.codes, 16, w.k, w.V, w.code_id, w.m, w.n, inp.lut)
     got_W = run_dequantize(q, w, inp)
-    for i in rows[::4]:
-        ref_row = np.array([oracle.decode_element(inp.codes, 16, w.k, w.V, w.code_id, w.n, int(i),
-                                                  j, inp.lut) for j in range(0, w.n, 7)],
-                           dtype=np.uint16)
-        assert np.array_equal(got_W[i, ::7], ref_row)
-    if w.m * w.n <= 4096 * 4096:
-        ref_W = oracle.dequantize(inp.codes, 16, w.k, w.V, w.code_id, w.m, w.n, inp.lut)
-        assert np.array_equal(got_W, ref_W)
+    assert got_W.shape == ref_W.shape and np.array_equal(got_W, ref_W)
     del got_W
-    # products: sampled outputs computed one by one by the oracle
-    ref = oracle.decode_matmat_rows(inp.codes, 16, w.k, w.V, w.code_id, w.m, w.n, inp.X, rows,
-                                    inp.lut, scale=inp.row_scale)
+    ref = oracle.matmat_dense(ref_W, inp.X, inp.row_scale)
+    del ref_W
+    gc.collect()
     got = run_matmat(q, w, inp)
-    assert np.all(np.isfinite(got))
-    err = float(np.abs(got[:, rows] - ref).max() / np.abs(ref).max())
-    assert err <= REL_TOL and err <= OBSERVED_TOL, err
+    assert got.shape == ref.shape == (w.B, w.m) and np.all(np.isfinite(got))
+    assert_products_match(got, ref)
     if w.B == 1 and not w.row_scale:
         got_mv = run_matmat(q, w, inp, use_matvec=True, scale=False)
         assert np.array_equal(got_mv, got)          # same kernel, deterministic
