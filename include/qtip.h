@@ -152,6 +152,26 @@ int qtip_rht_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_
                            void *xt_scratch_f16, void *stream);
 
 /*
+ * qtip_rht_decode_matvec for callers that cannot bring a scratch buffer and must not cause an
+ * allocation: code recorded under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments without xt_scratch, same kernels, same y bit for bit.
+ * The transformed activation of the two-kernel form lives in a buffer of the library's own, a
+ * static device array of QTIP_NOALLOC_MAX_N fp16 values (128 KiB, held on every GPU the
+ * library is used on until the process ends); n above QTIP_NOALLOC_MAX_N is QTIP_EINVAL.
+ * The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library
+ * routine): the array's device address is looked up once per device, on the first call
+ * there (QTIP_EHIP if that fails).  The buffer is written before it is read in every call,
+ * so nothing is cleared.  All calls on one GPU share it: two calls that overlap on one GPU
+ * (different streams, or graphs replayed concurrently) race and give wrong results; calls
+ * ordered on one stream are safe.
+ */
+#define QTIP_NOALLOC_MAX_N 65536
+int qtip_rht_decode_matvec_noalloc(const uint32_t *codes, int L, int k, int V, int code_id,
+                                   const void *lut_f16, int m, int n, const void *x_f16,
+                                   const int8_t *signs_n, int block, const void *row_scale_f16,
+                                   float *y, void *stream);
+
+/*
  * Decode only (for testing): W_f16[i][j] = W~[i][j], device, m x n row-major fp16,
  * no row scale.  Bit-exact with the definitions of Algorithms 1-3.
  */

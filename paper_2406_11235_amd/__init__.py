@@ -8,6 +8,7 @@ from .binding import (CODE_1MAD, CODE_3INST, CODE_HYB, CODE_HYB2, CODE_LUT, CODE
                       qtip_dequantize, qtip_last_error, qtip_quantize, qtip_quantize_gpu,
                       qtip_quantize_gpu_workspace, qtip_block_ldl, qtip_block_ldl_workspace,
                       qtip_quantize_ldlq, qtip_quantize_ldlq_workspace, qtip_rht, qtip_rht_decode_matvec,
+                      qtip_rht_decode_matvec_noalloc,
                       qtip_rht_f32,
                       qtip_version)
 
@@ -15,4 +16,4 @@ __all__ = ["CODE_1MAD", "CODE_3INST", "CODE_HYB", "CODE_HYB2", "CODE_LUT", "CODE
            "qtip_decode_matmat", "qtip_decode_matvec", "qtip_decode_states", "qtip_dequantize",
            "qtip_last_error", "qtip_quantize", "qtip_quantize_gpu", "qtip_quantize_gpu_workspace",
            "qtip_block_ldl", "qtip_block_ldl_workspace", "qtip_quantize_ldlq", "qtip_quantize_ldlq_workspace",
-           "qtip_rht", "qtip_rht_decode_matvec", "qtip_rht_f32", "qtip_version"]
+           "qtip_rht", "qtip_rht_decode_matvec", "qtip_rht_decode_matvec_noalloc", "qtip_rht_f32", "qtip_version"]

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("QTIP_LIBRARY") or os.path.join(_HERE, "libqtip.so")
 _lib = None
 
-EXPORTS = ["qtip_rht", "qtip_rht_f32", "qtip_decode_matvec", "qtip_rht_decode_matvec", "qtip_decode_matmat",
+EXPORTS = ["qtip_rht", "qtip_rht_f32", "qtip_decode_matvec", "qtip_rht_decode_matvec",
+           "qtip_rht_decode_matvec_noalloc", "qtip_decode_matmat",
            "qtip_dequantize", "qtip_decode_states", "qtip_quantize",
            "qtip_quantize_gpu_workspace", "qtip_quantize_gpu", "qtip_block_ldl_workspace",
            "qtip_block_ldl", "qtip_quantize_ldlq_workspace", "qtip_quantize_ldlq", "qtip_last_error",
@@ -60,6 +61,8 @@ def lib():
         L.qtip_decode_matvec.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp]
         L.qtip_rht_decode_matvec.restype = i32
         L.qtip_rht_decode_matvec.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
+        L.qtip_rht_decode_matvec_noalloc.restype = i32
+        L.qtip_rht_decode_matvec_noalloc.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp, vp, i32, vp, vp, vp]
         L.qtip_decode_matmat.restype = i32
         L.qtip_decode_matmat.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp, i32, vp, vp, vp]
         L.qtip_dequantize.restype = i32
@@ -140,6 +143,13 @@ def qtip_rht_decode_matvec(codes, L, k, V, code_id, lut, m, n, x, signs_n, block
     return _check(lib().qtip_rht_decode_matvec(_ptr(codes), L, k, V, code_id, _ptr(lut), m, n, _ptr(x),
                                                _ptr(signs_n), block, _ptr(row_scale), _ptr(y),
                                                _ptr(xt_scratch), _stream(stream)))
+
+
+def qtip_rht_decode_matvec_noalloc(codes, L, k, V, code_id, lut, m, n, x, signs_n, block, row_scale, y,
+                                   stream=None):
+    return _check(lib().qtip_rht_decode_matvec_noalloc(_ptr(codes), L, k, V, code_id, _ptr(lut), m, n, _ptr(x),
+                                                       _ptr(signs_n), block, _ptr(row_scale), _ptr(y),
+                                                       _stream(stream)))
 
 
 def qtip_decode_matmat(codes, L, k, V, code_id, lut, m, n, X, B, row_scale, Y, stream=None):

@@ -1,7 +1,9 @@
 // extern "C" entry points of include/qtip.h: argument validation, error strings,
 // and dispatch to the kernel launchers.  Nothing here touches the data.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
 #include <new>
 
 #include "../../include/qtip.h"
@@ -28,6 +30,38 @@ int hip_fail(const char *what, hipError_t e) {
 }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Scratch of qtip_rht_decode_matvec_noalloc: the transformed activation between its two
+// kernels.  One copy per GPU, at an address of its own on each; the name below is only a
+// host-side handle, the device address comes from hipGetSymbolAddress (noalloc_scratch()).
+static __device__ __align__(256) unsigned char scratch[QTIP_NOALLOC_MAX_N * 2];
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr
+// with the error string set.
+void *noalloc_scratch(const char *fn) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        hip_fail(fn, e);
+        return nullptr;
+    }
+    if (dev < 0 || dev >= MAX_DEVICES) {
+        fail(QTIP_EHIP, "%s: device index %d is outside the %d this library keeps scratch for", fn, dev, MAX_DEVICES);
+        return nullptr;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            hip_fail(fn, e);
+            return nullptr;
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // racing threads store the same address
+    }
+    return p;
+}
 
 // The (L, k, V, code) combinations that are built, the table the HYB codes need, and the
 // matrix shape: shared by every call that reads or writes a code stream.
@@ -137,6 +171,27 @@ int qtip_rht_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_
     }
     if (e != hipSuccess) return hip_fail(fn, e);
     return QTIP_OK;
+}
+
+int qtip_rht_decode_matvec_noalloc(const uint32_t *codes, int L, int k, int V, int code_id,
+                                   const void *lut_f16, int m, int n, const void *x_f16,
+                                   const int8_t *signs_n, int block, const void *row_scale_f16, float *y,
+                                   void *stream) {
+    const char *fn = "qtip_rht_decode_matvec_noalloc";
+    if (n > QTIP_NOALLOC_MAX_N)
+        return fail(QTIP_EINVAL, "%s: n = %d is above QTIP_NOALLOC_MAX_N = %d, the size of the library's own "
+                    "scratch; use qtip_rht_decode_matvec with a buffer of the caller's", fn, n, QTIP_NOALLOC_MAX_N);
+    void *xt = noalloc_scratch(fn);
+    if (!xt) return QTIP_EHIP;
+    const int rc = qtip_rht_decode_matvec(codes, L, k, V, code_id, lut_f16, m, n, x_f16, signs_n, block,
+                                          row_scale_f16, y, xt, stream);
+    if (rc != QTIP_OK) {  // same checks, this entry point's name in the message
+        char msg[sizeof(g_err)];
+        snprintf(msg, sizeof(msg), "%s", g_err);
+        const char *colon = strchr(msg, ':');
+        fail(rc, "%s%s", fn, colon ? colon : msg);
+    }
+    return rc;
 }
 
 int qtip_decode_matmat(const uint32_t *codes, int L, int k, int V, int code_id, const void *lut_f16,

@@ -5,6 +5,8 @@
 #include "qtip_internal.h"
 
 extern "C" const char *hipGetErrorString(hipError_t) { return "stub"; }
+extern "C" hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
+extern "C" hipError_t hipGetSymbolAddress(void **p, const void *symbol) { *p = const_cast<void *>(symbol); return hipSuccess; }
 
 namespace qtip {
 

@@ -37,7 +37,9 @@ def sanitized(tmp_path_factory):
     if not os.path.exists(CLANG) or asan_runtime() is None:
         pytest.skip("no clang with a shared AddressSanitizer runtime")
     out = tmp_path_factory.mktemp("san")
-    cxx = [CLANG + "++", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-I" + CSRC] + SAN
+    # (the two macros are the ones a plain C++ compile of the HIP headers leaves undefined)
+    cxx = [CLANG + "++", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-D__align__(n)=__attribute__((aligned(n)))",
+           "-DHIP_SYMBOL(x)=x", "-I/opt/rocm/include", "-I" + CSRC] + SAN
     objs = []
     for src, extra in (("qtip_api.hip", ["-x", "c++"]), ("qtip_quantize.cpp", ["-pthread"]),
                        (os.path.join(ROOT, "tests", "sanitize", "stub_launchers.cpp"), [])):
