@@ -91,6 +91,64 @@ def test_code_table_all_states_bit_exact(q, code_id, V):
     assert np.array_equal(got, ref)
 
 
+def all_states_stream():
+    """A 1024 x 256 matrix at k = 4, V = 1 whose streams carry every 16-bit state: tile t holds
+    the 64 values 64 t .. 64 t + 63 as consecutive 16-bit pieces, which are the states of the
+    sequence elements 0, 4, 8, ... (columns 0, 4, 8, 12 of every tile row)."""
+    vals = np.arange(65536, dtype=np.uint32).reshape(1024, 32, 2)
+    return (vals[:, :, 0] << 16) | vals[:, :, 1]           # MSB-first words: earlier piece in the high half
+
+
+@pytest.mark.parametrize("code_id", [CODE_1MAD, CODE_3INST, CODE_HYB1])
+def test_hot_loops_produce_the_code_values_for_every_state(q, code_id):
+    """The batch-1 and the matrix-core kernels decode with instruction sequences of their own,
+    not with the plain definitions behind qtip_decode_states and qtip_dequantize.  One-hot
+    activations bring single weights out of them unchanged (w * 1 plus zeros, fp32): every
+    one of the 2^16 states, through both kernels, must give exactly the oracle's code value."""
+    import torch
+    m, n, k = 1024, 256, 4
+    rng = np.random.default_rng(77)
+    lut = rng.standard_normal(64).astype(np.float16) if code_id == CODE_HYB1 else None
+    codes = all_states_stream()
+    Wref = oracle.dequantize(codes, 16, k, 1, code_id, m, n, lut).view(np.float16).astype(np.float32)
+    C = oracle.codebook(16, 1, code_id, lut)[:, 0].astype(np.float32)
+    cols = np.array([16 * J + c for J in range(16) for c in (0, 4, 8, 12)])
+    # the construction does what it says: those columns hold all 2^16 code values, in order
+    assert np.array_equal(Wref[:, cols].reshape(64, 16, 16, 4).transpose(0, 2, 1, 3).reshape(-1), C)
+    X = np.zeros((64, n), dtype=np.float16)
+    X[np.arange(64), cols] = 1.0
+    dc, dl, dX = dev(codes), dev(lut), dev(X)
+    Y = torch.full((64, m), float("nan"), dtype=torch.float32, device="cuda")
+    q.qtip_decode_matmat(dc, 16, k, 1, code_id, dl, m, n, dX, 64, None, Y)
+    y1 = torch.full((64, m), float("nan"), dtype=torch.float32, device="cuda")
+    for b in range(64):
+        q.qtip_decode_matvec(dc, 16, k, 1, code_id, dl, m, n, dX[b], y1[b])
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), Wref[:, cols].T)
+    assert np.array_equal(y1.cpu().numpy(), Wref[:, cols].T)
+
+
+@pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
+def test_hot_loops_produce_the_code_values_on_random_streams(q, code_id, k, V):
+    """The same through every codec's own extraction (k = 2, 3, 4; V = 2 as well): random
+    streams, one-hot activations for all 32 columns of a 512 x 32 matrix."""
+    import torch
+    m, n = 512, 32
+    w = small_workload(code_id, k, V, m, n, sub=77)
+    inp = synth.make_inputs(w)
+    Wref = oracle.dequantize(inp.codes, 16, k, V, code_id, m, n, inp.lut).view(np.float16).astype(np.float32)
+    X = np.eye(n, dtype=np.float16)
+    dc, dl, dX = dev(inp.codes), dev(inp.lut), dev(X)
+    Y = torch.full((n, m), float("nan"), dtype=torch.float32, device="cuda")
+    q.qtip_decode_matmat(dc, 16, k, V, code_id, dl, m, n, dX, n, None, Y)
+    y1 = torch.full((n, m), float("nan"), dtype=torch.float32, device="cuda")
+    for b in range(n):
+        q.qtip_decode_matvec(dc, 16, k, V, code_id, dl, m, n, dX[b], y1[b])
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), Wref.T)
+    assert np.array_equal(y1.cpu().numpy(), Wref.T)
+
+
 # ----------------------------------------------------------------- dequantize
 
 @pytest.mark.parametrize("code_id,k,V", ALL_CODECS)
