@@ -109,9 +109,14 @@ int qtip_rht_f32(const float *x_f32, const int8_t *signs, int n, int block, int 
  * decode each tile's bitstream to fp16 weights and contract with the activation):
  *   y[i] = sum_j W~[i][j] * x[j],   i < m, j < n.
  * x_f16: device, n fp16 (normally the output of qtip_rht side 0).  y: device, m
- * fp32, overwritten.  Decoded weights are exactly the fp16 values of
- * qtip_dequantize; products are accumulated in fp32.  lut_f16 is NULL unless
- * the code has a table (QTIP_CODE_HYB, QTIP_CODE_HYB2, QTIP_CODE_HYB1, QTIP_CODE_LUT).
+ * fp32, overwritten.  The weights are exactly the fp16 values of qtip_dequantize and
+ * every product is accumulated in fp32, with one exception: QTIP_CODE_1MAD at batch 1
+ * contracts with the quotient (s - 510) / 147.8 that Algorithm 1 returns, not with its
+ * fp16 rounding (the sum over j of (s_j - 510) x_j is formed first and divided once), so y
+ * differs from the product with the fp16 values by the rounding of the weights: at most
+ * 2^-12 relative per weight, about 2e-4 of the largest output on whole layers, against the
+ * fp64 product with the unrounded quotients about 1e-6.  lut_f16 is NULL unless the code
+ * has a table (QTIP_CODE_HYB, QTIP_CODE_HYB2, QTIP_CODE_HYB1, QTIP_CODE_LUT).
  */
 int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
                        const void *lut_f16, int m, int n, const void *x_f16, float *y,
@@ -121,7 +126,8 @@ int qtip_decode_matvec(const uint32_t *codes, int L, int k, int V, int code_id,
  * Batched form: Y[b][i] = row_scale[i] * sum_j W~[i][j] * X[b][j], b < B.
  * X_f16: device, B x n row-major fp16.  Y: device, B x m row-major fp32,
  * overwritten.  row_scale_f16: device, m fp16, or NULL for no scale.  B >= 1.
- * B = 1 runs the batch-1 kernel on the vector ALUs; every B >= 2 runs on the matrix cores
+ * B = 1 runs the batch-1 kernel on the vector ALUs (for QTIP_CODE_1MAD with the unrounded
+ * quotient, as qtip_decode_matvec); every B >= 2 runs on the matrix cores
  * (MFMA) with the decoded 16x16 tile as one operand (Section 4: T_x = T_y = 16 matches a
  * 16x16 matrix-multiply tile; with QTIP_CODE_LUT two neighbouring 32 x 8 blocks are the
  * 32 x 16 operand of the 32x32x16 instruction).  Y must be 16-byte aligned (and m a multiple

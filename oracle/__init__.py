@@ -61,6 +61,10 @@ def lib():
         L.orc_state.argtypes = [vp, i32, i32, i32, i32]
         L.orc_code_1mad.restype = c.c_uint16
         L.orc_code_1mad.argtypes = [c.c_uint32]
+        L.orc_code_1mad_real.restype = dbl
+        L.orc_code_1mad_real.argtypes = [c.c_uint32]
+        L.orc_dequantize_1mad_real.restype = i32
+        L.orc_dequantize_1mad_real.argtypes = [vp, i32, i32, i32, vp]
         L.orc_code_3inst.restype = c.c_uint16
         L.orc_code_3inst.argtypes = [c.c_uint32]
         L.orc_code_hyb.restype = None
@@ -168,6 +172,21 @@ def state(words, nbits, L, kV, t):
 
 def code_1mad(x):
     return int(lib().orc_code_1mad(int(x)))
+
+
+def code_1mad_real(x):
+    """Algorithm 1's quotient (s - 510) / 147.8, unrounded (float64)."""
+    return float(lib().orc_code_1mad_real(int(x)))
+
+
+def dequantize_1mad_real(codes, k, m, n):
+    """Dense 1MAD weights as Algorithm 1's unrounded quotients, float64 (m, n)."""
+    codes = _u32(codes).reshape(-1)
+    assert codes.size == (m // 16) * (n // 16) * 8 * k
+    W = np.zeros((m, n), dtype=np.float64)
+    rc = lib().orc_dequantize_1mad_real(_p(codes), k, m, n, _p(W))
+    assert rc == 0
+    return W
 
 
 def code_3inst(x):

@@ -147,6 +147,17 @@ uint16_t orc_code_1mad(uint32_t x) {
     return orc_f64_to_f16(w);
 }
 
+/*
+ * Algorithm 1 as printed: the value it returns is the quotient (s - 510) / 147.8 itself; the
+ * paper names no storage type for it.  orc_code_1mad above is this value rounded to fp16.
+ */
+double orc_code_1mad_real(uint32_t x) {
+    uint32_t X = 34038481u * x + 76625530u;
+    int s = (int)(X & 255u) + (int)((X >> 8) & 255u) + (int)((X >> 16) & 255u) +
+            (int)((X >> 24) & 255u);
+    return ((double)s - 510.0) / 147.8;
+}
+
 /* Algorithm 2 ("3INST"), a = 89226354, b = 64248484, m = fp16(0.922). */
 uint16_t orc_code_3inst(uint32_t x) {
     uint32_t X = 89226354u * x + 64248484u;
@@ -284,6 +295,27 @@ int orc_dequantize_tiled(const uint32_t *codes, int L, int k, int V, int code_id
                 W[(size_t)(Tx * I + s / Ty) * n + (Ty * J + s % Ty)] = seq[s];
         }
     }
+    return 0;
+}
+
+/*
+ * The 1MAD matrix with Algorithm 1's unrounded quotients as weights (16 x 16 tiles, L = 16,
+ * V = 1), dense row-major doubles: the reference for products that do not go through fp16
+ * weights.  Same stream walk and placement as orc_dequantize_tiled.
+ */
+int orc_dequantize_1mad_real(const uint32_t *codes, int k, int m, int n, double *W) {
+    if (m % 16 || n % 16) return -1;
+    const int T = 256, L = 16;
+    int wpt = k * T / 32;
+    int tn = n / 16;
+#pragma omp parallel for schedule(static)
+    for (int I = 0; I < m / 16; I++)
+        for (int J = 0; J < tn; J++) {
+            const uint32_t *tile = codes + ((size_t)I * tn + J) * wpt;
+            for (int s = 0; s < T; s++)
+                W[(size_t)(16 * I + s / 16) * n + (16 * J + s % 16)] =
+                    orc_code_1mad_real(orc_state(tile, k * T, L, k, s));
+        }
     return 0;
 }
 

@@ -210,6 +210,7 @@ __global__ __launch_bounds__(NW * 64, CODE == CODE_HYB1 ? 4 : 8) void matvec_ker
             compute(opB, Jb + TPI);
         }
     }
+    rd.finish(acc);
     // lanes with equal q hold partial sums of the same rows: add over g
 #pragma unroll
     for (int rr = 0; rr < RPL; rr++)

@@ -119,6 +119,41 @@ def _consts(golden):
     return {r[0]: r[1] for r in golden("code_constants.txt")}
 
 
+def test_1mad_unrounded_quotient(golden):
+    """Algorithm 1's returned value before any rounding: exact rationals 5 (s - 510) / 739 from the
+    constants the paper prints (Python integers, no floating point on the way), three states
+    worked by hand, its relation to the fp16 code value, and the dense-matrix form of it."""
+    from fractions import Fraction
+    c = _consts(golden)
+    a, b = int(c["1mad_a"]), int(c["1mad_b"])
+    scale = Fraction(c["1mad_scale"])              # 147.8 = 739 / 5, exactly
+    assert scale == Fraction(739, 5)
+
+    def quotient(x):
+        X = (a * x + b) % (1 << 32)
+        s = sum((X >> (8 * i)) & 255 for i in range(4))
+        return s, (Fraction(s) - int(c["1mad_shift"])) / scale
+    # hand-worked: x = 0 gives X = 0x0491367A, bytes 0x04 + 0x91 + 0x36 + 0x7A = 325
+    assert quotient(0)[0] == 325 and quotient(1)[0] == 386 and quotient(65535)[0] == 571
+    for x in list(range(0, 65536, 97)) + [1, 65535]:
+        s, q = quotient(x)
+        got = oracle.code_1mad_real(x)
+        assert abs(Fraction(got) - q) <= abs(q) * Fraction(1, 1 << 52), x      # correctly rounded to binary64
+        assert oracle.f64_to_f16(got) == oracle.code_1mad(x)                  # the fp16 code is its rounding
+        if q != 0:
+            assert abs(Fraction(oracle.f16_to_f64(oracle.code_1mad(x))) - q) <= abs(q) * Fraction(1, 1 << 11)
+    # the dense form walks the stream like dequantize
+    rng = np.random.default_rng(12)
+    for k in (2, 3, 4):
+        codes = rng.integers(0, 1 << 32, (2 * 3, 8 * k), dtype=np.uint64).astype(np.uint32)
+        Wr = oracle.dequantize_1mad_real(codes, k, 32, 48)
+        Wh = oracle.dequantize(codes, 16, k, 1, CODE_1MAD, 32, 48)
+        assert np.array_equal(Wr.astype(np.float16).view(np.uint16), Wh)
+        i, j = 17, 35
+        st = oracle.state(codes[(i // 16) * 3 + j // 16], 256 * k, 16, k, (i % 16) * 16 + j % 16)
+        assert Wr[i, j] == oracle.code_1mad_real(st)
+
+
 def test_1mad_table_against_numpy_and_closed_form(golden):
     c = _consts(golden)
     a, b = int(c["1mad_a"]), int(c["1mad_b"])
