@@ -397,17 +397,18 @@ def ldlq_feedback_f32(W, E, A, j, g=16):
     return x
 
 
-def ldlq_quantize_f32(W, A, L, k, V, code_id, lut=None, rounder=None, tile=(16, 16)):
+def ldlq_quantize_f32(W, A, L, k, V, code_id, lut=None, rounder=None, tile=(16, 16), table=None):
     """Algorithm 5 with tile = (T_x, T_y): column blocks of T_y from the last to the first,
     feedback in binary32 (ldlq_feedback_f32), every T_x x T_y block of x rounded as one sequence
     by the binary32 tail-biting quantizer.  Returns (codes (tiles, 8k), What float32, x of every
-    block).  `rounder(S) -> (value, words)` replaces the quantizer (tests)."""
+    block).  `rounder(S) -> (value, words)` replaces the quantizer, `table` (2^L x V values) the
+    code's own codebook (tests of the loop's identities on a small trellis)."""
     W, A = _f32(W), _f32(A)
     m, n = W.shape
     Tx, Ty = tile
     assert Tx * Ty == 256
     tn = n // Ty
-    C = codebook(L, V, code_id, lut)
+    C = codebook(L, V, code_id, lut) if table is None else _f64(table).reshape(1 << L, V)
     codes = np.zeros(((m // Tx) * tn, 8 * k), dtype=np.uint32)
     What = np.zeros((m, n), dtype=np.float32)
     E = np.zeros((m, n), dtype=np.float32)

@@ -686,13 +686,8 @@ def test_ldlq_loop_identities(Tx, Ty):
     def rounder(S):
         return oracle.tailbiting_quantize_f32(S, L, k, V, C8)
 
-    import oracle as o
-    orig = o.codebook
-    try:
-        o.codebook = lambda *a, **kw: C8                     # a table code at L = 8 keeps this fast
-        codes, What, xs = o.ldlq_quantize_f32(W, A, L, k, V, CODE_3INST, rounder=rounder, tile=(Tx, Ty))
-    finally:
-        o.codebook = orig
+    # a table code at L = 8 keeps this fast
+    codes, What, xs = oracle.ldlq_quantize_f32(W, A, L, k, V, CODE_3INST, rounder=rounder, tile=(Tx, Ty), table=C8)
     E = W.astype(np.float64) - What
     eta = xs.astype(np.float64) - What
     assert np.allclose(E @ (np.eye(n) + A.astype(np.float64)), eta, rtol=1e-4, atol=1e-4)
