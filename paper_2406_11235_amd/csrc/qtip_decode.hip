@@ -260,9 +260,9 @@ __device__ __forceinline__ void load_row_words(const uint32_t *__restrict__ tile
     constexpr int NWORDS = 8 * K;
     const int bit = 16 * K * i;
     const int w0 = bit >> 5;
-    w[0] = tile[w0];
-    w[1] = tile[(w0 + 1) % NWORDS];
-    w[2] = (K == 2) ? 0u : tile[(w0 + 2) % NWORDS];
+    w[0] = stream_load(tile + w0);
+    w[1] = stream_load(tile + (w0 + 1) % NWORDS);
+    w[2] = (K == 2) ? 0u : stream_load(tile + (w0 + 2) % NWORDS);
 }
 template <int K>
 __device__ __forceinline__ void align_row_words(int i, uint32_t (&w)[3]) {

@@ -234,8 +234,8 @@ __global__ __launch_bounds__(NW * 64) void lut_matmat_kernel(const uint32_t *__r
     auto issue = [&](int Jb) {
         const int J = min(Jb + s, Jend - 1);  // a half past the end re-reads the last block
         const uint32_t *tile = codes + ((size_t)I * tn + J) * NWORDS;
-        wn[0] = tile[w0];
-        wn[1] = tile[(w0 + 1) % NWORDS];  // wraps inside the block (tail-biting)
+        wn[0] = stream_load(tile + w0);
+        wn[1] = stream_load(tile + (w0 + 1) % NWORDS);  // wraps inside the block (tail-biting)
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) {
             const int b = b0 + 32 * nb + i;
@@ -356,8 +356,8 @@ __global__ __launch_bounds__(NW * 64) void lut_matmat_staged_kernel(const uint32
     auto issue_w = [&](int Jb) {
         const int J = min(Jb + s, Jend - 1);  // a half past the end re-reads the last block
         const uint32_t *tile = codes + ((size_t)I * tn + J) * NWORDS;
-        wn[0] = tile[w0];
-        wn[1] = tile[(w0 + 1) % NWORDS];  // wraps inside the block (tail-biting)
+        wn[0] = stream_load(tile + w0);
+        wn[1] = stream_load(tile + (w0 + 1) % NWORDS);  // wraps inside the block (tail-biting)
     };
     auto decode = [&](half8_t &a) {
         const uint64_t both = (((uint64_t)wn[0] << 32) | wn[1]) << sh;
