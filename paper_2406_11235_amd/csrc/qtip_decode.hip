@@ -456,11 +456,13 @@ static hipError_t launch_dequantize_t(const uint32_t *codes, const uint32_t *lut
 // grid has m/16 workgroups and NW decides both how many waves the chip gets and how
 // many steps each wave runs: few steps leave a wave's start-up and reduction exposed,
 // few waves leave SIMDs idle or the vector ALU short of waves to interleave.
-static int pick_matvec_waves(int tm, int steps_per_row) {
-    (void)tm;
-    // measured on the configured shapes: occupancy matters more than steps per wave;
-    // 16 waves win once a wave still gets 4 steps, 8 are best for mid-sized rows
-    if (steps_per_row >= 64) return 16;
+// Measured by kernel durations from the profiler's trace (for kernels this short a loop
+// of launches from the host times the host): as many waves as there are steps, up to 16,
+// is best everywhere: 4096 x 4096 (16 steps) 6.0 us with 8 waves, 5.4 with 16; 14336 x 4096
+// 11.6 -> 11.3.  The kernel that transforms its own input keeps 8 for such rows: it has
+// the transform's registers on top and spills under the cap that 16 waves put on it.
+static int pick_matvec_waves(int steps_per_row, bool fused) {
+    if (steps_per_row >= (fused ? 64 : 16)) return 16;
     if (steps_per_row >= 8) return 8;
     if (steps_per_row >= 4) return 4;
     return 2;
@@ -479,7 +481,7 @@ static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, in
                                   float *y, hipStream_t st) {
     constexpr int TPI = 64 / Geo<K>::LPT;
     const int tm = m / 16, tn = n / 16;
-    const int nw = pick_matvec_waves(tm, (tn + TPI - 1) / TPI);
+    const int nw = pick_matvec_waves((tn + TPI - 1) / TPI, signs != nullptr);
     const bool spread = pick_hyb_spread(CODE, n);
     // signs != null: x is untransformed and the kernel transforms it itself (n <= FUSED_MAX_N)
 #define QTIP_MV_LAUNCH3(NW, FUSED, SPREAD)                                                                 \
