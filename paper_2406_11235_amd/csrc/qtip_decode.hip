@@ -125,9 +125,11 @@ constexpr int FUSED_MAX_N = 8192;
 // filling per workgroup, and pays on long rows.  (Eight waves per SIMD, i.e. at most 64
 // registers: the loop needs no more, and a second workgroup per CU is worth more than the few
 // values that spill around it.)
-// (The V = 1 hash code keeps a whole tile's table reads in flight and needs more registers.)
+// (The V = 1 hash code keeps a whole tile's table reads in flight and needs more registers; the
+// kernel that transforms its own input runs with at most one workgroup per CU, four waves per
+// SIMD, and may take the registers that leaves it.)
 template <int K, int V, int CODE, int NW, bool FUSED, bool SPREAD = false>
-__global__ __launch_bounds__(NW * 64, CODE == CODE_HYB1 ? 4 : 8) void matvec_kernel(const uint32_t *__restrict__ codes,
+__global__ __launch_bounds__(NW * 64, (CODE == CODE_HYB1 || FUSED) ? 4 : 8) void matvec_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
                                                          int tn, const half_t *__restrict__ x,
                                                          const int8_t *__restrict__ signs, int log2_block,
@@ -459,10 +461,10 @@ static hipError_t launch_dequantize_t(const uint32_t *codes, const uint32_t *lut
 // Measured by kernel durations from the profiler's trace (for kernels this short a loop
 // of launches from the host times the host): as many waves as there are steps, up to 16,
 // is best everywhere: 4096 x 4096 (16 steps) 6.0 us with 8 waves, 5.4 with 16; 14336 x 4096
-// 11.6 -> 11.3.  The kernel that transforms its own input keeps 8 for such rows: it has
-// the transform's registers on top and spills under the cap that 16 waves put on it.
-static int pick_matvec_waves(int steps_per_row, bool fused) {
-    if (steps_per_row >= (fused ? 64 : 16)) return 16;
+// 11.6 -> 11.3.  The kernel that transforms its own input takes the same count, so that it
+// adds its partial sums in the same order and gives the same bits as the two separate calls.
+static int pick_matvec_waves(int steps_per_row) {
+    if (steps_per_row >= 16) return 16;
     if (steps_per_row >= 8) return 8;
     if (steps_per_row >= 4) return 4;
     return 2;
@@ -481,7 +483,7 @@ static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, in
                                   float *y, hipStream_t st) {
     constexpr int TPI = 64 / Geo<K>::LPT;
     const int tm = m / 16, tn = n / 16;
-    const int nw = pick_matvec_waves((tn + TPI - 1) / TPI, signs != nullptr);
+    const int nw = pick_matvec_waves((tn + TPI - 1) / TPI);
     const bool spread = pick_hyb_spread(CODE, n);
     // signs != null: x is untransformed and the kernel transforms it itself (n <= FUSED_MAX_N)
 #define QTIP_MV_LAUNCH3(NW, FUSED, SPREAD)                                                                 \
