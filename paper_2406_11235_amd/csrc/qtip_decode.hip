@@ -161,11 +161,15 @@ __global__ __launch_bounds__(NW * 64, (CODE == CODE_HYB1 || FUSED) ? 4 : 8) void
     typename RowDotFor<K, CODE, SPREAD>::type rd;
     rd.init(s_lut);
     const int I = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // the wave's number as a scalar: its tile range and the loop over it then live in scalar
+    // registers and the loop control costs no vector instructions
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int g = lane / LPT, q = lane & (LPT - 1);
     const int chunk = ((tn + NW * TPI - 1) / (NW * TPI)) * TPI;
     const int J0 = wave * chunk;
     const int Jend = min(tn, J0 + chunk);
+    // this tile row's words: a uniform base, so that a lane's address is base + 32-bit offset
+    const uint32_t *__restrict__ row_codes = codes + (size_t)I * tn * (8 * K);
     float acc[RPL];
 #pragma unroll
     for (int rr = 0; rr < RPL; rr++) acc[rr] = 0.f;
@@ -178,16 +182,16 @@ __global__ __launch_bounds__(NW * 64, (CODE == CODE_HYB1 || FUSED) ? 4 : 8) void
         uint4 xa, xb;
     };
     auto issue = [&](Operands &o, int Jb) {
-        const int Jc = min(Jb + g, Jend - 1);  // lanes past the end re-read the last tile
-        o.w = load_words<K>(codes, (size_t)I * tn + Jc, q);
+        const uint32_t Jc = min(Jb + g, Jend - 1);  // lanes past the end re-read the last tile
+        o.w = load_words<K>(row_codes, Jc * (8 * K) + q * Geo<K>::WPL);
         if constexpr (FUSED) {
             const uint4 *xp = reinterpret_cast<const uint4 *>(s_x + 16 * Jc);
             o.xa = xp[0];
             o.xb = xp[1];
         } else {
-            const uint4 *xp = reinterpret_cast<const uint4 *>(x + 16 * Jc);
-            o.xa = xp[0];
-            o.xb = xp[1];
+            const uint4 *xp = reinterpret_cast<const uint4 *>(x);
+            o.xa = xp[2 * Jc];
+            o.xb = xp[2 * Jc + 1];
         }
     };
     auto compute = [&](const Operands &o, int Jb) {

@@ -76,12 +76,11 @@ __device__ __forceinline__ u32x4_t stream_load4(const uint32_t *p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
 }
 
-// This lane's WPL words of tile `tile` (q = lane's position inside the tile).
+// A lane's WPL words at word offset `off` from a base every lane shares.
 template <int K>
-__device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ codes, size_t tile,
-                                               int q) {
+__device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ base, uint32_t off) {
     constexpr int WPL = Geo<K>::WPL;
-    const uint32_t *p = codes + tile * (8 * K) + q * WPL;
+    const uint32_t *p = base + off;
     Words<K> r;
     if constexpr (WPL == 4) {
         const u32x4_t t = stream_load4(p);
@@ -90,6 +89,12 @@ __device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ code
         r.v[0] = stream_load(p); r.v[1] = stream_load(p + 1); r.v[2] = stream_load(p + 2);
     }
     return r;
+}
+// This lane's WPL words of tile `tile` (q = lane's position inside the tile).
+template <int K>
+__device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ codes, size_t tile,
+                                               int q) {
+    return load_words<K>(codes + tile * (8 * K), (uint32_t)(q * Geo<K>::WPL));
 }
 
 __device__ __forceinline__ half2_t as_half2(uint32_t v) {
@@ -106,14 +111,18 @@ __device__ __forceinline__ uint32_t window32(const uint32_t (&w)[NW], int P) {
     return __builtin_amdgcn_alignbit(w[i], w[i + 1], 32 - s);
 }
 
-// 16-bit window starting P bits into the word array w.
+// 16-bit window starting P bits into the word array w, zero-extended: one bit-field extract.
+// A window that crosses into the next word is taken from the 32 bits that start at bit 16 of
+// its word; that funnel shift is the same for every such window of the word (the compiler
+// keeps one), so a tile row of 16 windows costs one or two funnel shifts and 16 extracts.
 template <int NW>
 __device__ __forceinline__ uint32_t window16(const uint32_t (&w)[NW], int P) {
     const int i = P >> 5, s = P & 31;
     if (s == 0) return w[i] >> 16;
     if (s == 16) return w[i] & 0xFFFFu;
     if (s < 16) return (w[i] >> (16 - s)) & 0xFFFFu;
-    return __builtin_amdgcn_alignbit(w[i], w[i + 1], 48 - s) & 0xFFFFu;
+    const uint32_t m = __builtin_amdgcn_alignbit(w[i], w[i + 1], 16);
+    return (m >> (32 - s)) & 0xFFFFu;
 }
 
 // ------------------------------------------------------------------ plain codes
@@ -183,22 +192,8 @@ __device__ __forceinline__ uint32_t lcg_mad64(uint32_t x, uint32_t a, uint64_t b
 template <int K, int NW>
 __device__ __forceinline__ void row_states(const uint32_t (&w)[NW], int rr, uint32_t (&st)[16]) {
     const int P0 = rr * 16 * K;
-    if constexpr (K == 2 || K == 4) {
-        // windows 16 bits apart are 16/K weights apart: both halves of a 32-bit
-        // window are states
-        constexpr int G = 16 / K;  // weights between the two halves
 #pragma unroll
-        for (int base = 0; base < 16; base += 2 * G)
-#pragma unroll
-            for (int j = 0; j < G; j++) {
-                uint32_t R = window32(w, P0 + (base + j) * K);
-                st[base + j] = R >> 16;
-                st[base + j + G] = R & 0xFFFFu;
-            }
-    } else {
-#pragma unroll
-        for (int c = 0; c < 16; c++) st[c] = window16(w, P0 + c * K);
-    }
+    for (int c = 0; c < 16; c++) st[c] = window16(w, P0 + c * K);
 }
 
 // Two packed weight pairs from four 3INST words: p = (sum(y0), sum(y1)), q = (sum(y2),
