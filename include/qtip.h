@@ -43,7 +43,8 @@
  *   32, n of 8.  Anything else returns QTIP_EUNSUPPORTED / QTIP_EINVAL.
  *   Sizes: m, n and batch sizes are ints; every offset into codes, weights, activations
  *   and outputs is formed in 64 bits, so buffers may pass 4 GiB (checked on 98304 x 98304
- *   at 4 bits).  The calls that record nothing but kernel launches (all of the GPU entry
+ *   at 4 bits); only the position inside one tile row's code stream is kept in 32 bits,
+ *   which limits n to QTIP_MAX_N = 2^28 (above it: QTIP_EINVAL).  The calls that record nothing but kernel launches (all of the GPU entry
  *   points) may be captured into a HIP graph.
  *
  * OWNERSHIP, STREAMS, ERRORS
@@ -72,6 +73,8 @@ extern "C" {
 #define QTIP_EUNSUPPORTED (-2) /* (L, k, V, code_id) outside the supported set  */
 #define QTIP_EHIP (-3)         /* HIP runtime / launch failure                  */
 #define QTIP_ENOMEM (-4)       /* host allocation failed (qtip_quantize)        */
+
+#define QTIP_MAX_N (1 << 28) /* largest number of columns any entry point takes */
 
 #define QTIP_CODE_1MAD 0  /* Algorithm 1 */
 #define QTIP_CODE_3INST 1 /* Algorithm 2 */

@@ -83,6 +83,8 @@ int check_code(const char *fn, int L, int k, int V, int code_id, const void *lut
     const int tx = is_lut(code_id) ? 32 : 16, ty = is_lut(code_id) ? 8 : 16;
     if (m <= 0 || n <= 0 || m % tx || n % ty)
         return fail(QTIP_EINVAL, "%s: m = %d must be a positive multiple of %d, n = %d of %d", fn, m, tx, n, ty);
+    // the kernels address the code stream of one tile row with 32-bit byte offsets (n k / 2 bytes)
+    if (n > QTIP_MAX_N) return fail(QTIP_EINVAL, "%s: n = %d is above QTIP_MAX_N = %d", fn, n, QTIP_MAX_N);
     return QTIP_OK;
 }
 

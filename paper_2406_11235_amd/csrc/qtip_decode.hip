@@ -183,15 +183,16 @@ __global__ __launch_bounds__(NW * 64, (CODE == CODE_HYB1 || FUSED) ? 4 : 8) void
     };
     auto issue = [&](Operands &o, int Jb) {
         const uint32_t Jc = min(Jb + g, Jend - 1);  // lanes past the end re-read the last tile
-        o.w = load_words<K>(row_codes, Jc * (8 * K) + q * Geo<K>::WPL);
+        // (byte offsets in 32 bits from uniform bases: the loads take them as they are)
+        o.w = load_words_at<K>(row_codes, Jc * (32 * K) + q * (4 * Geo<K>::WPL));
         if constexpr (FUSED) {
             const uint4 *xp = reinterpret_cast<const uint4 *>(s_x + 16 * Jc);
             o.xa = xp[0];
             o.xb = xp[1];
         } else {
-            const uint4 *xp = reinterpret_cast<const uint4 *>(x);
-            o.xa = xp[2 * Jc];
-            o.xb = xp[2 * Jc + 1];
+            const uint4 *xp = reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(x) + (size_t)(Jc * 32u));
+            o.xa = xp[0];
+            o.xb = xp[1];
         }
     };
     auto compute = [&](const Operands &o, int Jb) {

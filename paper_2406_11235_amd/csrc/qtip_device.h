@@ -90,6 +90,20 @@ __device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ base
     }
     return r;
 }
+// The same with a byte offset.
+template <int K>
+__device__ __forceinline__ Words<K> load_words_at(const uint32_t *__restrict__ base, uint32_t byte_off) {
+    constexpr int WPL = Geo<K>::WPL;
+    const uint32_t *p = reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + (size_t)byte_off);
+    Words<K> r;
+    if constexpr (WPL == 4) {
+        const u32x4_t t = stream_load4(p);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+        r.v[0] = stream_load(p); r.v[1] = stream_load(p + 1); r.v[2] = stream_load(p + 2);
+    }
+    return r;
+}
 // This lane's WPL words of tile `tile` (q = lane's position inside the tile).
 template <int K>
 __device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ codes, size_t tile,

@@ -62,6 +62,7 @@ def test_argument_errors_need_no_gpu(q):
         (L.qtip_decode_matvec(p, 16, 2, 2, 2, None, 16, 16, p, p, None), EINVAL),
         (L.qtip_decode_matvec(p, 16, 2, 1, 7, None, 16, 16, p, p, None), EUNSUP),
         (L.qtip_decode_matvec(p + 4, 16, 2, 1, 1, None, 16, 16, p, p, None), EINVAL),
+        (L.qtip_decode_matvec(p, 16, 2, 1, 1, None, 16, (1 << 28) + 16, p, p, None), EINVAL),   # above QTIP_MAX_N
         (L.qtip_decode_matvec(p, 16, 2, 1, 4, p, 32, 16, p, p, None), EUNSUP),       # the lookup-only code: L = 14
         (L.qtip_decode_matvec(p, 14, 2, 1, 4, None, 32, 16, p, p, None), EINVAL),   # needs its table
         (L.qtip_decode_matvec(p, 14, 2, 1, 4, p + 4, 32, 16, p, p, None), EINVAL),  # 16-byte aligned
