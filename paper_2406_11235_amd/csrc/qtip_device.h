@@ -433,8 +433,16 @@ template <int K> struct RowDot<K, CODE_3INST> {
                                         float &acc) const {
         uint32_t st[16], y[16];
         row_states<K>(w, rr, st);
+        // (a multiply-add needs a wait state before the next instruction that reads its result,
+        // and before another multiply-add: each mask + xor goes behind the next multiply-add)
+        uint32_t X = lcg_mad64(st[0], INST_A, b64);
 #pragma unroll
-        for (int c = 0; c < 16; c++) y[c] = (lcg_mad64(st[c], INST_A, b64) & INST_MASK) ^ mm;
+        for (int c = 1; c < 16; c++) {
+            const uint32_t Xn = lcg_mad64(st[c], INST_A, b64);
+            y[c - 1] = (X & INST_MASK) ^ mm;
+            X = Xn;
+        }
+        y[15] = (X & INST_MASK) ^ mm;
         // Software-pipelined by groups of four weights: a group's two dot products are
         // issued at the head of the next group's block, so that every block ends with four
         // SDWA adds and the dot unit's results are old enough (three wait states) before any
