@@ -6,11 +6,13 @@
 // code_1mad, code_hyb) are the definitions written out; dequantize, the
 // state-table test entry and the MFMA path use them.  The RowDot structs are
 // the batch-1 hot loop: one tile row (16 weights) decoded and contracted with 16
-// activations, arranged around what the vector ALU issues fastest on this chip
-// (measured: and/or/xor/shift-right/add/v_add_f16 run at twice the rate of
-// three-operand integer ops; v_mad_u64_u32 and v_mul_lo_u32 are full rate):
-//   * two states per funnel shift: with 16-bit states, the high and low halves
-//     of a 32-bit window at a multiple of k*V bits are both states;
+// activations, in as few vector instructions as the exact codes allow (in the
+// kernel, where eight waves in different phases share a SIMD, every vector
+// instruction costs about four cycles whatever its kind):
+//   * a zero-extended state is one v_bfe_u32, from its word or from one funnel
+//     shift per word for the states that cross into the next word;
+//   * the HYB codes hash two states at once: with 16-bit states, the high and low
+//     halves of a 32-bit window at a multiple of k*V bits are both states;
 //   * the LCG a*x+b (mod 2^32) is one v_mad_u64_u32 on the zero-extended state;
 //   * mask+xor is one v_bitop3_b32;
 //   * the fp16 add of the two halves writes straight into one half of a packed
