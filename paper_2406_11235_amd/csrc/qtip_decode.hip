@@ -114,6 +114,47 @@ __global__ void decode_states_kernel(const uint32_t *__restrict__ states, int co
 
 // ------------------------------------------------------- decode + matvec (B = 1)
 
+// A value of the lane `off` lanes away (lane ^ off), any off < 64.
+__device__ __forceinline__ float lane_xor(float v, int lane, int off) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ off) << 2, __builtin_bit_cast(int, v)));
+}
+// v + the value of the lane N places further round this lane's row of 16 (a DPP row rotate).
+template <int N> __device__ __forceinline__ float add_row_ror(float v) {
+    return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xF, 0xF, false));
+}
+// The end of the batch-1 kernels: lane = g * LPT + q holds RPL partial sums, rows q * RPL + rr
+// of the tile row, and the 64 / LPT lanes with the same q are to be added up.  Over lane bits 5
+// and 4 the lanes trade sums instead of each adding all of them: a lane hands the partner the
+// rows the partner keeps and adds what it gets to the rows it keeps itself, so the number of
+// sums per lane halves with every exchange (three cross-lane reads at RPL = 4, two at RPL = 2,
+// where adding everything everywhere takes sixteen and six); the lane bits below 4 are summed
+// with row rotates inside the vector ALU.  On return acc[0] is the whole sum for row
+// q * RPL + (return value), the same in all lanes that differ only in the lane bits below 4
+// that belong to g.
+template <int LPT, int RPL>
+__device__ __forceinline__ int reduce_over_tile_groups(float (&acc)[RPL], int lane) {
+    static_assert((LPT == 4 && RPL == 4) || (LPT == 8 && RPL == 2), "tile geometries of Geo<K>");
+    const bool b5 = lane & 32, b4 = lane & 16;
+    float v;
+    if constexpr (RPL == 4) {
+        // bit 5 clear keeps rows 0 and 1, set keeps rows 2 and 3
+        const float r0 = lane_xor(b5 ? acc[0] : acc[2], lane, 32), r1 = lane_xor(b5 ? acc[1] : acc[3], lane, 32);
+        const float v0 = (b5 ? acc[2] : acc[0]) + r0, v1 = (b5 ? acc[3] : acc[1]) + r1;
+        // bit 4 clear keeps the first of the two, set the second
+        v = (b4 ? v1 : v0) + lane_xor(b4 ? v0 : v1, lane, 16);
+        v = add_row_ror<8>(v);
+        v = add_row_ror<4>(v);
+        acc[0] = v;
+        return (b5 ? 2 : 0) + (b4 ? 1 : 0);
+    } else {
+        v = (b5 ? acc[1] : acc[0]) + lane_xor(b5 ? acc[0] : acc[1], lane, 32);
+        v += lane_xor(v, lane, 16);
+        v = add_row_ror<8>(v);
+        acc[0] = v;
+        return b5 ? 1 : 0;
+    }
+}
+
 // FUSED: x is the untransformed activation and the workgroup first computes the input-side
 // random Hadamard transform V (S .* x) of Section 2.1 into LDS itself (every workgroup the
 // whole vector: at most 8192 values, about 2 us, against a kernel launch and the gap to
@@ -219,14 +260,8 @@ __global__ __launch_bounds__(NW * 64, (CODE == CODE_HYB1 || FUSED) ? 4 : 8) void
     }
     rd.finish(acc);
     // lanes with equal q hold partial sums of the same rows: add over g
-#pragma unroll
-    for (int rr = 0; rr < RPL; rr++)
-#pragma unroll
-        for (int off = LPT; off < 64; off <<= 1) acc[rr] += __shfl_xor(acc[rr], off, 64);
-    if (g == 0) {
-#pragma unroll
-        for (int rr = 0; rr < RPL; rr++) s_part[wave][q * RPL + rr] = acc[rr];
-    }
+    const int rr_mine = reduce_over_tile_groups<LPT, RPL>(acc, lane);
+    if ((g & (16 / LPT - 1)) == 0) s_part[wave][q * RPL + rr_mine] = acc[0];
     __syncthreads();
     if (threadIdx.x < 16) {
         float s = 0.f;
