@@ -169,14 +169,14 @@ constexpr int FUSED_MAX_N = 8192;
 // (The V = 1 hash code keeps a whole tile's table reads in flight and needs more registers; the
 // kernel that transforms its own input runs with at most one workgroup per CU, four waves per
 // SIMD, and may take the registers that leaves it.)
-template <int K, int V, int CODE, int NW, bool FUSED, bool SPREAD = false>
+template <int K, int V, int CODE, int NW, bool FUSED, bool SPREAD = false, bool WIDE = false>
 __global__ __launch_bounds__(NW * 64, (CODE == CODE_HYB1 || FUSED) ? 4 : 8) void matvec_kernel(const uint32_t *__restrict__ codes,
                                                          const uint32_t *__restrict__ lut,
                                                          int tn, const half_t *__restrict__ x,
                                                          const int8_t *__restrict__ signs, int log2_block,
                                                          const half_t *__restrict__ scale,
                                                          float *__restrict__ y) {
-    constexpr int WPL = Geo<K>::WPL, LPT = Geo<K>::LPT, RPL = Geo<K>::RPL;
+    constexpr int WPL = MvGeo<K, WIDE>::WPL, LPT = MvGeo<K, WIDE>::LPT, RPL = MvGeo<K, WIDE>::RPL;
     constexpr int TPI = 64 / LPT;  // tiles per wave per iteration
     __shared__ __attribute__((aligned(16))) uint32_t s_lut[code_lds_words(CODE, SPREAD)];
     __shared__ float s_part[NW][16];
@@ -219,13 +219,13 @@ __global__ __launch_bounds__(NW * 64, (CODE == CODE_HYB1 || FUSED) ? 4 : 8) void
     // Two operand sets alternate (the loop body is two steps), so nothing is copied
     // (3-4 % on the computed codes, measured against the copying form on one box).
     struct Operands {
-        Words<K> w;
+        WordsN<WPL> w;
         uint4 xa, xb;
     };
     auto issue = [&](Operands &o, int Jb) {
         const uint32_t Jc = min(Jb + g, Jend - 1);  // lanes past the end re-read the last tile
         // (byte offsets in 32 bits from uniform bases: the loads take them as they are)
-        o.w = load_words_at<K>(row_codes, Jc * (32 * K) + q * (4 * Geo<K>::WPL));
+        o.w = load_words_at<WPL>(row_codes, Jc * (32 * K) + q * (4 * WPL));
         if constexpr (FUSED) {
             const uint4 *xp = reinterpret_cast<const uint4 *>(s_x + 16 * Jc);
             o.xa = xp[0];
@@ -523,27 +523,41 @@ static hipError_t launch_matvec_t(const uint32_t *codes, const uint32_t *lut, in
                                   float *y, hipStream_t st) {
     constexpr int TPI = 64 / Geo<K>::LPT;
     const int tm = m / 16, tn = n / 16;
-    const int nw = pick_matvec_waves((tn + TPI - 1) / TPI);
+    const int steps = (tn + TPI - 1) / TPI;
+    const int nw = pick_matvec_waves(steps);
     const bool spread = pick_hyb_spread(CODE, n);
     // signs != null: x is untransformed and the kernel transforms it itself (n <= FUSED_MAX_N)
-#define QTIP_MV_LAUNCH3(NW, FUSED, SPREAD)                                                                 \
-    hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW, FUSED, SPREAD>), dim3(tm), dim3(NW * 64), 0, st, codes, \
-                       lut, tn, (const half_t *)x, signs, log2_block, (const half_t *)scale, y)
-#define QTIP_MV_LAUNCH(NW)                                \
-    if (signs)                                            \
-        QTIP_MV_LAUNCH3(NW, true, false);                 \
-    else if (code_is_hyb(CODE) && spread)                 \
-        QTIP_MV_LAUNCH3(NW, false, code_is_hyb(CODE));    \
-    else                                                  \
-        QTIP_MV_LAUNCH3(NW, false, false)
+#define QTIP_MV_LAUNCH4(NW, FUSED, SPREAD, WIDE)                                                            \
+    hipLaunchKernelGGL((matvec_kernel<K, V, CODE, NW, FUSED, SPREAD, WIDE>), dim3(tm), dim3(NW * 64), 0, st, \
+                       codes, lut, tn, (const half_t *)x, signs, log2_block, (const half_t *)scale, y)
+#define QTIP_MV_LAUNCH(NW, WIDE)                                \
+    if (signs)                                                  \
+        QTIP_MV_LAUNCH4(NW, true, false, WIDE);                 \
+    else if (code_is_hyb(CODE) && spread)                       \
+        QTIP_MV_LAUNCH4(NW, false, code_is_hyb(CODE), WIDE);    \
+    else                                                        \
+        QTIP_MV_LAUNCH4(NW, false, false, WIDE)
+    // Four rows per lane at k = 3 and 4 (MvGeo<K, true>: steps of 16 tiles) where 16 waves still have a
+    // step each and the row splits into such steps as evenly as into the narrow ones (measured, k = 4:
+    // 14336 x 4096 12.44 -> 11.38 us, 8192 x 8192 HYB 10.64 -> 10.38; 4096 x 14336, 896 tiles = 3.5 wide
+    // steps per wave, 11.76 -> 12.10 us, so it keeps the narrow form).  The choice depends on the row
+    // length alone, so the kernel that transforms its own input makes the same one.
+    if constexpr (K != 2) {
+        constexpr int WTPI = 64 / MvGeo<K, true>::LPT;
+        const int wsteps = (tn + WTPI - 1) / WTPI;
+        if (wsteps >= 16 && 2 * ((wsteps + 15) / 16) <= (steps + nw - 1) / nw) {
+            QTIP_MV_LAUNCH(16, true);
+            return hipGetLastError();
+        }
+    }
     switch (nw) {
-        case 2: QTIP_MV_LAUNCH(2); break;
-        case 4: QTIP_MV_LAUNCH(4); break;
-        case 16: QTIP_MV_LAUNCH(16); break;
-        default: QTIP_MV_LAUNCH(8); break;
+        case 2: QTIP_MV_LAUNCH(2, false); break;
+        case 4: QTIP_MV_LAUNCH(4, false); break;
+        case 16: QTIP_MV_LAUNCH(16, false); break;
+        default: QTIP_MV_LAUNCH(8, false); break;
     }
 #undef QTIP_MV_LAUNCH
-#undef QTIP_MV_LAUNCH3
+#undef QTIP_MV_LAUNCH4
     return hipGetLastError();
 }
 

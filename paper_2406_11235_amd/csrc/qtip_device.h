@@ -73,6 +73,7 @@ template <> struct Words<4> { uint32_t v[4]; };
 // (measured over rotating buffers: 8192 x 28672 2-bit 3INST 34.3 -> 34.0 us, HYB 21.4 -> 20.7,
 // 8192 x 8192 4-bit HYB 11.9 -> 11.4, 14336 x 4096 4-bit 1MAD 13.0 -> 12.8).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t stream_load(const uint32_t *p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ u32x4_t stream_load4(const uint32_t *p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
@@ -92,17 +93,35 @@ __device__ __forceinline__ Words<K> load_words(const uint32_t *__restrict__ base
     }
     return r;
 }
-// The same with a byte offset.
-template <int K>
-__device__ __forceinline__ Words<K> load_words_at(const uint32_t *__restrict__ base, uint32_t byte_off) {
-    constexpr int WPL = Geo<K>::WPL;
+// The batch-1 kernel's second spread of a tile over lanes (WIDE): at k = 3 and 4 a lane takes
+// four tile rows like at k = 2 (six or eight words, four lanes per tile), so that the work
+// around a step (offsets, loads, the wrap read, the end test) is shared by 64 weights per lane
+// instead of 32.  A step then covers 16 tiles, and rows whose tile count does not split evenly
+// into such steps over the waves keep the narrow form (the launcher chooses).
+template <int K, bool WIDE> struct MvGeo : Geo<K> {};
+template <> struct MvGeo<3, true> { static constexpr int WPL = 6, LPT = 4, RPL = 4; };
+template <> struct MvGeo<4, true> { static constexpr int WPL = 8, LPT = 4, RPL = 4; };
+template <int WPL> struct WordsN { uint32_t v[WPL]; };
+// A lane's WPL words at byte offset `byte_off` from a base every lane shares.
+template <int WPL>
+__device__ __forceinline__ WordsN<WPL> load_words_at(const uint32_t *__restrict__ base, uint32_t byte_off) {
     const uint32_t *p = reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + (size_t)byte_off);
-    Words<K> r;
-    if constexpr (WPL == 4) {
-        const u32x4_t t = stream_load4(p);
-        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    WordsN<WPL> r;
+    if constexpr (WPL % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < WPL; i += 4) {
+            const u32x4_t t = stream_load4(p + i);
+            r.v[i] = t.x; r.v[i + 1] = t.y; r.v[i + 2] = t.z; r.v[i + 3] = t.w;
+        }
+    } else if constexpr (WPL % 2 == 0) {  // six words: 8-byte aligned
+#pragma unroll
+        for (int i = 0; i < WPL; i += 2) {
+            const u32x2_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(p + i));
+            r.v[i] = t.x; r.v[i + 1] = t.y;
+        }
     } else {
-        r.v[0] = stream_load(p); r.v[1] = stream_load(p + 1); r.v[2] = stream_load(p + 2);
+#pragma unroll
+        for (int i = 0; i < WPL; i++) r.v[i] = stream_load(p + i);
     }
     return r;
 }
